@@ -1,0 +1,212 @@
+"""Pins for the oracle's converters (Section II-C formats, Section III-C sub-tasks, Section IV-C tile width)."""
+import json
+import os
+
+import numpy as np
+import pytest
+import scipy.sparse as sp
+
+import oracle
+from paper_2604_17834_amd import synth
+
+
+def densify_bits(a: synth.Csr) -> np.ndarray:
+    d = np.zeros((a.m, a.k), dtype=a.values.dtype)
+    for i in range(a.m):
+        for p in range(a.row_ptr[i], a.row_ptr[i + 1]):
+            d[i, a.col_idx[p]] = a.values[p]
+    return d
+
+
+def stored_mask(a: synth.Csr) -> np.ndarray:
+    d = np.zeros((a.m, a.k), dtype=bool)
+    for i in range(a.m):
+        d[i, a.col_idx[a.row_ptr[i]:a.row_ptr[i + 1]]] = True
+    return d
+
+
+# ------------------------------------------------------------------ golden
+def test_golden_formats(golden_dir):
+    g = json.load(open(os.path.join(golden_dir, "formats_4x6_example.json")))
+    rp, ci = np.array(g["row_ptr"]), np.array(g["col_idx"])
+    va = np.array(g["values"], dtype=np.float32)
+    brp, bci, blocks = oracle.to_bcsr(g["m"], g["k"], rp, ci, va, "f32", g["b_row"], g["b_col"])
+    assert brp.tolist() == g["bcsr"]["block_row_ptr"]
+    assert bci.tolist() == g["bcsr"]["block_col_idx"]
+    assert blocks.tolist() == g["bcsr"]["blocks"]
+    assert oracle.fill_ratio(len(va), len(bci), 2, 2) == g["bcsr"]["fill_ratio"]
+    wrp, wci, vals = oracle.to_wcsr(g["m"], g["k"], rp, ci, va, "f32", g["b_row"], g["b_col"])
+    assert wrp.tolist() == g["wcsr"]["window_row_ptr"]
+    assert wci.tolist() == g["wcsr"]["window_col_idx"]
+    assert vals.tolist() == g["wcsr"]["values"]
+    assert oracle.wcsr_tasks(wrp, 2).tolist() == g["tasks_task_cols_2"]
+    assert oracle.wcsr_tasks(wrp, 4).tolist() == g["tasks_task_cols_4"]
+
+
+def test_golden_tile_width(golden_dir):
+    g = json.load(open(os.path.join(golden_dir, "tile_width_examples.json")))
+    for c in g["cases"]:
+        pad = oracle.padded_width(g["N"], c["BN"])
+        assert pad == c["padded"]
+        assert round(100 * (pad - g["N"]) / g["N"]) == c["waste_percent"]
+    assert oracle.choose_bn(1024, [64, 128, 256, 352, 496, 512]) == 512
+    assert oracle.choose_bn(1024, [352, 496]) == 352       # none divides: least padding
+    assert oracle.choose_bn(192, [64, 128, 256]) == 64     # largest divisor, not largest width
+    assert oracle.choose_bn(16384, [64, 128, 256]) == 256
+
+
+# ------------------------------------------------------------------ BCSR
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("m,k,br,bc,density", [(64, 96, 16, 32, 0.02), (128, 128, 32, 32, 0.01),
+                                               (60, 60, 4, 6, 0.1), (32, 64, 32, 64, 0.001)])
+def test_bcsr_vs_scipy_tobsr(dtype, m, k, br, bc, density):
+    a = synth.random_csr(m, k, density, 7, dtype, empty_row_frac=0.3)
+    brp, bci, blocks = oracle.to_bcsr(a.m, a.k, a.row_ptr, a.col_idx, a.values, dtype, br, bc)
+    # scipy works on floats: carry the bit patterns as exact small integers + 1 so that no stored entry is 0
+    carrier = a.values.astype(np.float64) + 1.0 if dtype == "bf16" else a.values.astype(np.float64)
+    M = sp.csr_matrix((carrier, a.col_idx, a.row_ptr), shape=(m, k))
+    bsr = M.tobsr(blocksize=(br, bc))
+    bsr.sort_indices()
+    assert np.array_equal(brp, bsr.indptr)
+    assert np.array_equal(bci, bsr.indices)
+    if dtype == "bf16":
+        mask = bsr.data != 0
+        back = np.where(mask, bsr.data - 1.0, 0.0)
+        assert np.array_equal(blocks.astype(np.float64), back)
+    else:
+        assert np.array_equal(blocks.astype(np.float64), bsr.data)
+
+
+@pytest.mark.parametrize("m,k,br,bc", [(10, 13, 4, 4), (33, 65, 32, 32), (5, 5, 8, 8), (17, 9, 4, 2)])
+def test_bcsr_ragged_vs_dense_brute_force(m, k, br, bc):
+    a = synth.random_csr(m, k, 0.15, 9, "bf16")
+    D, Mk = densify_bits(a), stored_mask(a)
+    brp, bci, blocks = oracle.to_bcsr(m, k, a.row_ptr, a.col_idx, a.values, "bf16", br, bc)
+    nbr, nbc = -(-m // br), -(-k // bc)
+    q = 0
+    for I in range(nbr):
+        assert brp[I] == q
+        for J in range(nbc):
+            sub = Mk[I * br:(I + 1) * br, J * bc:(J + 1) * bc]
+            if sub.any():
+                assert bci[q] == J
+                tile = np.zeros((br, bc), dtype=D.dtype)
+                s = D[I * br:(I + 1) * br, J * bc:(J + 1) * bc]
+                tile[:s.shape[0], :s.shape[1]] = s
+                assert np.array_equal(blocks[q], tile)
+                q += 1
+    assert brp[nbr] == q == len(bci)
+
+
+def test_bcsr_explicit_zero_is_structural():
+    # a stored 0.0 keeps its block (the converter never looks at values)
+    brp, bci, blocks = oracle.to_bcsr(2, 4, np.array([0, 1, 1]), np.array([3]), np.array([0.0], np.float32),
+                                      "f32", 2, 2)
+    assert brp.tolist() == [0, 1] and bci.tolist() == [1] and not blocks.any()
+
+
+def test_bcsr_full_mask_is_tiled_dense():
+    a = synth.block_sparse_bernoulli(64, 96, 16, 32, 0.0, 3)
+    brp, bci, blocks = oracle.to_bcsr(a.m, a.k, a.row_ptr, a.col_idx, a.values, "bf16", 16, 32)
+    assert len(bci) == 4 * 3 and brp.tolist() == [0, 3, 6, 9, 12]
+    D = densify_bits(a)
+    tiled = D.reshape(4, 16, 3, 32).transpose(0, 2, 1, 3).reshape(12, 16, 32)
+    assert np.array_equal(blocks, tiled)
+    assert oracle.fill_ratio(a.nnz, len(bci), 16, 32) == 1.0
+
+
+def test_fill_ratio_formula():
+    assert oracle.fill_ratio(6, 4, 2, 2) == 6 / 16
+    assert oracle.fill_ratio(0, 0, 64, 64) == 0.0
+    assert oracle.fill_ratio(4096, 1, 64, 64) == 1.0
+
+
+# ------------------------------------------------------------------ WCSR
+def decode_wcsr(m, k, b_row, b_col, wrp, wci, vals):
+    D = np.zeros((m, k), dtype=vals.dtype)
+    for w in range(len(wrp) - 1):
+        for p in range(wrp[w], wrp[w + 1]):
+            c = wci[p]
+            if c < 0:
+                continue
+            T, lane = divmod(p, b_col)
+            for r in range(b_row):
+                i = w * b_row + r
+                if i < m:
+                    D[i, c] = vals[T, r, lane]
+    return D
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("m,k,br,bc,density", [(64, 80, 16, 8, 0.05), (50, 33, 16, 8, 0.2), (37, 64, 8, 4, 0.1),
+                                               (64, 64, 64, 8, 0.02), (9, 100, 32, 8, 0.3)])
+def test_wcsr_round_trip_and_invariants(dtype, m, k, br, bc, density):
+    a = synth.random_csr(m, k, density, 13, dtype, empty_row_frac=0.25)
+    wrp, wci, vals = oracle.to_wcsr(m, k, a.row_ptr, a.col_idx, a.values, dtype, br, bc)
+    nw = -(-m // br)
+    assert len(wrp) == nw + 1 and wrp[0] == 0
+    assert vals.shape == (wrp[-1] // bc, br, bc) and len(wci) == wrp[-1]
+    Mk, D = stored_mask(a), densify_bits(a)
+    for w in range(nw):
+        seg = wci[wrp[w]:wrp[w + 1]]
+        assert len(seg) % bc == 0
+        real = seg[seg >= 0]
+        assert np.all(np.diff(real) > 0)                      # strictly ascending
+        assert np.all(seg[len(real):] == -1) and len(seg) - len(real) < bc   # pads at the tail, minimal
+        cols_here = np.nonzero(Mk[w * br:(w + 1) * br].any(axis=0))[0]
+        assert np.array_equal(real, cols_here)                # exactly the union of the window's columns
+        # pad columns carry all-zero bits
+        for t in range(len(real), len(seg)):
+            T, lane = divmod(wrp[w] + t, bc)
+            assert not vals[T, :, lane].any()
+    assert np.array_equal(decode_wcsr(m, k, br, bc, wrp, wci, vals), D)
+    # nothing but the stored entries is nonzero in the tiles
+    assert np.count_nonzero(vals) == np.count_nonzero(a.values)
+
+
+def test_wcsr_1x1_is_csr_itself():
+    a = synth.random_csr(40, 50, 0.1, 17, "f32", empty_row_frac=0.2)
+    wrp, wci, vals = oracle.to_wcsr(a.m, a.k, a.row_ptr, a.col_idx, a.values, "f32", 1, 1)
+    assert np.array_equal(wrp, a.row_ptr)
+    assert np.array_equal(wci, a.col_idx)
+    assert np.array_equal(vals.reshape(-1), a.values)
+
+
+def test_wcsr_single_window_dense_column_union():
+    # two rows sharing a column: the shared column is stored once, both rows' values side by side
+    rp, ci = np.array([0, 2, 4]), np.array([1, 3, 3, 4])
+    va = np.array([10, 20, 30, 40], dtype=np.float32)
+    wrp, wci, vals = oracle.to_wcsr(2, 6, rp, ci, va, "f32", 2, 4)
+    assert wrp.tolist() == [0, 4] and wci.tolist() == [1, 3, 4, -1]
+    assert vals.tolist() == [[[10, 20, 0, 0], [0, 30, 40, 0]]]
+
+
+# ------------------------------------------------------------------ tasks
+@pytest.mark.parametrize("task_cols", [8, 16, 64, 4096])
+def test_tasks_tile_each_window(task_cols):
+    a = synth.zipf_graph(512, 512, 16 * 512, seed=5, cap=300)
+    wrp, _, _ = oracle.to_wcsr(a.m, a.k, a.row_ptr, a.col_idx, a.values, "f32", 16, 8)
+    tasks = oracle.wcsr_tasks(wrp, task_cols)
+    t = 0
+    for w in range(len(wrp) - 1):
+        pos = wrp[w]
+        n_here = 0
+        while t < len(tasks) and tasks[t, 0] == w:
+            assert tasks[t, 1] == pos
+            width = tasks[t, 2] - tasks[t, 1]
+            assert 0 < width <= task_cols
+            pos = tasks[t, 2]
+            if pos != wrp[w + 1]:
+                assert width == task_cols                     # only the last may be short
+            n_here += 1
+            t += 1
+        assert pos == wrp[w + 1]
+        assert n_here == -(-(wrp[w + 1] - wrp[w]) // task_cols)
+        assert np.all(tasks[t - n_here:t, 3] == (1 if n_here > 1 else 0))
+    assert t == len(tasks)
+    if task_cols >= np.diff(wrp).max():
+        assert len(tasks) == np.count_nonzero(np.diff(wrp)) and not tasks[:, 3].any()
+
+
+def test_tasks_empty():
+    assert oracle.wcsr_tasks(np.array([0, 0, 0]), 8).shape == (0, 4)
