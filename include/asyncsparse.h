@@ -1,0 +1,144 @@
+/*
+ * asyncsparse.h -- C ABI of the MI355X (gfx950) sparse-times-dense library.
+ *
+ * Computes C = A x B with A sparse (m x k), B dense (k x N), C dense (m x N)
+ * (paper, Section II-C, problem statement), with A re-stored either as Block
+ * Compressed Sparse Row (BCSR) or as Window Compressed Sparse Row (WCSR)
+ * (Section II-C, "Sparse Formats"), and WCSR row-windows cut into fixed-size
+ * sub-tasks for load balance (Section III-C, last paragraph).
+ *
+ * General rules
+ *   - Every call returns an asp_status_t.  Nothing throws, nothing aborts.
+ *     asp_last_error() gives a thread-local detail string for the last failure.
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device
+ *     memory of the GPU that was current when the handle was created.
+ *   - A handle is immutable after creation: concurrent asp_spmm calls on
+ *     different streams with different C buffers are safe.
+ *   - The library needs a gfx950 GPU for everything except the calls marked
+ *     "host only".  There is no CPU fallback for the product.
+ */
+#ifndef ASYNCSPARSE_H
+#define ASYNCSPARSE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct asp_handle asp_handle_t; /* opaque, owned by the library */
+
+typedef enum {
+    ASP_OK = 0,
+    ASP_ERR_INVALID_ARG = 1,      /* null pointer, non-positive size, misuse */
+    ASP_ERR_INVALID_CSR = 2,      /* CSR arrays are not a valid sorted CSR matrix */
+    ASP_ERR_UNSUPPORTED = 3,      /* block/window size, dtype or mode not built */
+    ASP_ERR_OUT_OF_MEMORY = 4,
+    ASP_ERR_HIP = 5,              /* a HIP runtime call failed (no GPU, launch error, ...) */
+    ASP_ERR_BUFFER_TOO_SMALL = 6  /* asp_export: dst_bytes < *needed */
+} asp_status_t;
+
+typedef enum { ASP_FMT_BCSR = 0, ASP_FMT_WCSR = 1 } asp_format_t;
+
+/* dtype of A's values, of B and of C.  Accumulation is always fp32 (MFMA). */
+typedef enum { ASP_DT_BF16 = 0, ASP_DT_F32 = 1 } asp_dtype_t;
+
+/* Convert on the host and keep host arrays only: no HIP call is made, so this works
+ * without a GPU.  The handle can be inspected (info/export/plan) but asp_spmm refuses it. */
+#define ASP_FLAG_HOST_CONVERT_ONLY 1u
+
+typedef struct {
+    int32_t format;    /* asp_format_t */
+    int32_t dtype;     /* asp_dtype_t; supported pairs: BCSR+bf16, WCSR+f32 */
+    int32_t b_row;     /* BCSR: block height in {32,64,128}; WCSR: window height in {16,32,64} */
+    int32_t b_col;     /* BCSR: block width, = b_row; WCSR: column padding unit, = 8 */
+    int32_t task_cols; /* WCSR: packed columns per sub-task, positive multiple of b_col; 0 = default (512) */
+    uint32_t flags;    /* ASP_FLAG_* */
+} asp_config_t;
+
+typedef struct {
+    int64_t m, k, nnz;
+    int32_t format, dtype, b_row, b_col, task_cols;
+    int32_t on_device;  /* 1 when the handle holds device arrays and asp_spmm can run */
+    int64_t n_brows;    /* block-rows (BCSR) or windows (WCSR) = ceil(m / b_row) */
+    int64_t n_units;    /* stored blocks (BCSR) or packed columns incl. pads (WCSR) */
+    int64_t n_tasks;    /* WCSR sub-tasks; 0 for BCSR */
+    int64_t n_zero_rows_units; /* WCSR: windows whose C rows are cleared before the kernel (empty or split) */
+    double fill_ratio;  /* nnz / stored value slots (Section II-C, fill ratio) */
+} asp_info_t;
+
+/* Which array asp_export copies out.  Layouts (all row-major, int32 indices):
+ *  BCSR (Section II-C):
+ *    ROW_PTR  block_row_ptr[n_brows+1]      first stored block of each block-row
+ *    COL_IDX  block_col_idx[n_units]        block column of each stored block, ascending in a block-row
+ *    VALUES   blocks[n_units][b_row][b_col] dense blocks, +0.0 where CSR stores nothing
+ *  WCSR (Section II-C):
+ *    ROW_PTR  window_row_ptr[n_brows+1]     first packed column of each window (multiples of b_col)
+ *    COL_IDX  window_col_idx[n_units]       original column of each packed column, ascending in a
+ *                                           window, -1 for the (< b_col) pads at a window's tail
+ *    VALUES   values[n_units/b_col][b_row][b_col]  one dense tile per b_col packed columns
+ *    TASKS    tasks[n_tasks][4] = {window, col_begin, col_end, split}  (Section III-C); packed-column
+ *             positions are absolute, col_end - col_begin = task_cols except for a window's last task,
+ *             split = 1 when the window has more than one task.  Tasks are in window order.
+ *  A block or a window column is stored when CSR holds an entry there, whatever its value.
+ */
+typedef enum { ASP_ARR_ROW_PTR = 0, ASP_ARR_COL_IDX = 1, ASP_ARR_VALUES = 2, ASP_ARR_TASKS = 3 } asp_array_t;
+
+/* How asp_spmm would run for a dense width N (Section IV-C: tile-width selection). */
+typedef struct {
+    int32_t bn;          /* columns of B/C handled by one workgroup (BCSR) or one wave (WCSR) */
+    int32_t n_tiles;     /* ceil(N / bn): tiles along N, the last one masked if bn does not divide N */
+    int32_t vectorized;  /* 1: 16-byte row accesses (needs N*sizeof(dtype) % 16 == 0 and 16-byte aligned B, C) */
+    int64_t workgroups;  /* workgroups of the main kernel */
+    int64_t padded_n;    /* n_tiles * bn: width actually computed on */
+} asp_plan_t;
+
+/*
+ * Build a handle from CSR (Section II-C).  CSR arrays are HOST pointers and are only read during
+ * the call.  Requirements: m, k >= 1; nnz >= 0; row_ptr[0] = 0, non-decreasing, row_ptr[m] = nnz;
+ * 0 <= col_idx < k and strictly ascending inside every row (duplicates are rejected, not summed);
+ * values are nnz elements of cfg->dtype (bf16 as uint16 bit patterns) and are only ever bit-copied.
+ * stream: hipStream_t used for uploads and the task-partition kernels (NULL = default stream); the
+ * call returns after they completed.  On error *out is NULL and nothing is leaked.
+ */
+asp_status_t asp_create_from_csr(const asp_config_t *cfg, int64_t m, int64_t k, int64_t nnz,
+                                 const int32_t *row_ptr, const int32_t *col_idx, const void *values,
+                                 void *stream, asp_handle_t **out);
+
+/*
+ * C = A x B (Section II-C; kernels: Sections III-A..III-C re-designed for gfx950).
+ * B: DEVICE, k x N row-major, leading dimension N.  C: DEVICE, m x N row-major, leading dimension N,
+ * fully overwritten (rows of A without entries become zeros); C must not alias B.
+ * N >= 1.  stream: hipStream_t (NULL = default).  Asynchronous: only enqueues kernels, never
+ * synchronises, never allocates.  bf16: fp32 accumulation, round-to-nearest-even to bf16 on store.
+ * f32 WCSR: windows that are split into several tasks are combined with fp32 atomic adds, so their
+ * rows may differ in the last bits from run to run; everything else is bitwise reproducible.
+ */
+asp_status_t asp_spmm(const asp_handle_t *h, const void *B, void *C, int64_t N, void *stream);
+
+/* host only: describe the handle */
+asp_status_t asp_get_info(const asp_handle_t *h, asp_info_t *info);
+
+/* host only: the launch shape asp_spmm would use for width N with 16-byte aligned B and C */
+asp_status_t asp_plan_spmm(const asp_handle_t *h, int64_t N, asp_plan_t *plan);
+
+/*
+ * Copy one canonical array (see asp_array_t) to HOST memory.  *needed (may be NULL) receives the
+ * size in bytes; when dst_bytes is smaller nothing is copied and ASP_ERR_BUFFER_TOO_SMALL returns
+ * (call with host_dst = NULL, dst_bytes = 0 to query).  Synchronises the device if it must read back.
+ */
+asp_status_t asp_export(const asp_handle_t *h, asp_array_t which, void *host_dst, size_t dst_bytes,
+                        size_t *needed);
+
+/* Frees host and device memory of the handle.  NULL is allowed. */
+asp_status_t asp_destroy(asp_handle_t *h);
+
+/* host only */
+const char *asp_status_string(asp_status_t s);
+const char *asp_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ASYNCSPARSE_H */

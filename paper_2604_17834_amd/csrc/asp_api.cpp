@@ -1,0 +1,270 @@
+// C ABI entry points: argument checking, handle life cycle, export.  See include/asyncsparse.h.
+#include <cstring>
+#include <new>
+
+#include "asp_internal.h"
+
+namespace asp {
+
+static thread_local std::string g_last_error;
+
+void set_error(const std::string &msg) { g_last_error = msg; }
+
+asp_status_t fail(asp_status_t s, const std::string &msg) {
+    g_last_error = msg;
+    return s;
+}
+
+static void free_device(asp_handle *h) {
+    if (h->device < 0) return;
+    int cur = -1;
+    (void)hipGetDevice(&cur);
+    if (cur != h->device) (void)hipSetDevice(h->device);
+    (void)hipFree(h->d_row_ptr);
+    (void)hipFree(h->d_col_idx);
+    (void)hipFree(h->d_values);
+    (void)hipFree(h->d_tasks);
+    (void)hipFree(h->d_zero_windows);
+    if (cur >= 0 && cur != h->device) (void)hipSetDevice(cur);
+}
+
+template <class T>
+static asp_status_t upload(T **dst, const void *src, size_t bytes, hipStream_t stream) {
+    *dst = nullptr;
+    ASP_HIP_TRY(hipMalloc((void **)dst, bytes > 0 ? bytes : 16));
+    if (bytes > 0) ASP_HIP_TRY(hipMemcpyAsync(*dst, src, bytes, hipMemcpyHostToDevice, stream));
+    return ASP_OK;
+}
+
+static asp_status_t create_impl(const asp_config_t *cfg, int64_t m, int64_t k, int64_t nnz,
+                                const int32_t *row_ptr, const int32_t *col_idx, const void *values,
+                                hipStream_t stream, asp_handle *h) {
+    h->m = m;
+    h->k = k;
+    h->nnz = nnz;
+    h->format = cfg->format;
+    h->dtype = cfg->dtype;
+    h->b_row = cfg->b_row;
+    h->b_col = cfg->b_col;
+    h->flags = cfg->flags;
+    h->n_brows = ceil_div(m, cfg->b_row);
+    const bool host_only = (cfg->flags & ASP_FLAG_HOST_CONVERT_ONLY) != 0;
+    const size_t es = dtype_size(cfg->dtype);
+
+    if (cfg->format == ASP_FMT_BCSR) {
+        h->task_cols = 0;
+        csr_to_bcsr(m, k, row_ptr, col_idx, values, es, cfg->b_row, cfg->b_col, h->hb);
+        h->n_units = (int64_t)h->hb.block_col_idx.size();
+        if (host_only) return ASP_OK;
+        bcsr_pack_fragments_bf16(h->hb, cfg->b_row, cfg->b_col, h->hb.packed);
+        ASP_HIP_TRY(hipGetDevice(&h->device));
+        asp_status_t s;
+        if ((s = upload(&h->d_row_ptr, h->hb.block_row_ptr.data(), h->hb.block_row_ptr.size() * 4, stream))) return s;
+        if ((s = upload(&h->d_col_idx, h->hb.block_col_idx.data(), h->hb.block_col_idx.size() * 4, stream))) return s;
+        if ((s = upload(&h->d_values, h->hb.packed.data(), h->hb.packed.size(), stream))) return s;
+        ASP_HIP_TRY(hipStreamSynchronize(stream));
+        std::vector<uint8_t>().swap(h->hb.packed);  // the device copy is the only user
+        return ASP_OK;
+    }
+
+    // WCSR
+    h->task_cols = cfg->task_cols > 0 ? cfg->task_cols : 512;
+    csr_to_wcsr(m, k, row_ptr, col_idx, values, es, cfg->b_row, cfg->b_col, h->hw);
+    h->n_units = (int64_t)h->hw.window_col_idx.size();
+    wcsr_zero_windows(h->hw.window_row_ptr, h->task_cols, h->hw.zero_windows);
+    h->n_zero_windows = (int64_t)h->hw.zero_windows.size();
+    if (host_only) {
+        wcsr_tasks_host(h->hw.window_row_ptr, h->task_cols, h->hw.tasks);
+        h->n_tasks = (int64_t)h->hw.tasks.size() / 4;
+        return ASP_OK;
+    }
+    ASP_HIP_TRY(hipGetDevice(&h->device));
+    asp_status_t s;
+    if ((s = upload(&h->d_row_ptr, h->hw.window_row_ptr.data(), h->hw.window_row_ptr.size() * 4, stream))) return s;
+    if ((s = upload(&h->d_col_idx, h->hw.window_col_idx.data(), h->hw.window_col_idx.size() * 4, stream))) return s;
+    if ((s = upload(&h->d_values, h->hw.values.data(), h->hw.values.size(), stream))) return s;
+    if ((s = upload(&h->d_zero_windows, h->hw.zero_windows.data(), h->hw.zero_windows.size() * 4, stream))) return s;
+    if ((s = wcsr_build_tasks_device(h, stream))) return s;  // wavefront-scan partition on the GPU
+    ASP_HIP_TRY(hipStreamSynchronize(stream));
+    // the device arrays are the canonical ones; drop the host copies (values can be gigabytes)
+    h->hw = HostWcsr();
+    return ASP_OK;
+}
+
+}  // namespace asp
+
+using namespace asp;
+
+extern "C" {
+
+asp_status_t asp_create_from_csr(const asp_config_t *cfg, int64_t m, int64_t k, int64_t nnz,
+                                 const int32_t *row_ptr, const int32_t *col_idx, const void *values,
+                                 void *stream, asp_handle_t **out) {
+    if (out) *out = nullptr;
+    if (!cfg || !out || !row_ptr) return fail(ASP_ERR_INVALID_ARG, "null cfg, out or row_ptr");
+    if (m < 1 || k < 1 || nnz < 0) return fail(ASP_ERR_INVALID_ARG, "need m >= 1, k >= 1, nnz >= 0");
+    if (m >= (1ll << 31) || k >= (1ll << 31) || nnz >= (1ll << 31))
+        return fail(ASP_ERR_UNSUPPORTED, "m, k and nnz must fit int32");
+    if (nnz > 0 && (!col_idx || !values)) return fail(ASP_ERR_INVALID_ARG, "null col_idx or values with nnz > 0");
+    if (cfg->flags & ~ASP_FLAG_HOST_CONVERT_ONLY) return fail(ASP_ERR_INVALID_ARG, "unknown flag bits");
+    if (cfg->format == ASP_FMT_BCSR) {
+        if (cfg->dtype != ASP_DT_BF16) return fail(ASP_ERR_UNSUPPORTED, "BCSR is built for bf16 only");
+        if (!(cfg->b_row == 32 || cfg->b_row == 64 || cfg->b_row == 128) || cfg->b_col != cfg->b_row)
+            return fail(ASP_ERR_UNSUPPORTED, "BCSR blocks must be 32x32, 64x64 or 128x128");
+    } else if (cfg->format == ASP_FMT_WCSR) {
+        if (cfg->dtype != ASP_DT_F32) return fail(ASP_ERR_UNSUPPORTED, "WCSR is built for f32 only");
+        if (!(cfg->b_row == 16 || cfg->b_row == 32 || cfg->b_row == 64) || cfg->b_col != 8)
+            return fail(ASP_ERR_UNSUPPORTED, "WCSR needs b_row in {16,32,64} and b_col = 8");
+        if (cfg->task_cols < 0 || cfg->task_cols % cfg->b_col != 0)
+            return fail(ASP_ERR_INVALID_ARG, "task_cols must be 0 or a positive multiple of b_col");
+    } else {
+        return fail(ASP_ERR_INVALID_ARG, "unknown format");
+    }
+    std::string why = validate_csr(m, k, nnz, row_ptr, col_idx);
+    if (!why.empty()) return fail(ASP_ERR_INVALID_CSR, why);
+
+    asp_handle *h = nullptr;
+    asp_status_t s;
+    try {
+        h = new asp_handle();
+        s = create_impl(cfg, m, k, nnz, row_ptr, col_idx, values, (hipStream_t)stream, h);
+        // sizes that the kernels index with int32
+        if (s == ASP_OK && h->n_units >= (1ll << 31)) s = fail(ASP_ERR_UNSUPPORTED, "too many blocks / packed columns");
+    } catch (const std::bad_alloc &) {
+        s = fail(ASP_ERR_OUT_OF_MEMORY, "host allocation failed during conversion");
+    } catch (const std::exception &e) {
+        s = fail(ASP_ERR_INVALID_ARG, std::string("conversion failed: ") + e.what());
+    }
+    if (s != ASP_OK) {
+        if (h) {
+            free_device(h);
+            delete h;
+        }
+        return s;
+    }
+    *out = h;
+    return ASP_OK;
+}
+
+asp_status_t asp_spmm(const asp_handle_t *h, const void *B, void *C, int64_t N, void *stream) {
+    if (!h || !B || !C) return fail(ASP_ERR_INVALID_ARG, "null handle, B or C");
+    if (N < 1) return fail(ASP_ERR_INVALID_ARG, "N must be >= 1");
+    if (h->device < 0) return fail(ASP_ERR_UNSUPPORTED, "handle was converted on the host only; it has no device arrays");
+    if (N >= (1ll << 31) || h->m * N >= (1ll << 40)) return fail(ASP_ERR_UNSUPPORTED, "N too large");
+    if (h->format == ASP_FMT_BCSR) return bcsr_spmm_launch(h, B, C, N, (hipStream_t)stream);
+    return wcsr_spmm_launch(h, B, C, N, (hipStream_t)stream);
+}
+
+asp_status_t asp_get_info(const asp_handle_t *h, asp_info_t *info) {
+    if (!h || !info) return fail(ASP_ERR_INVALID_ARG, "null handle or info");
+    info->m = h->m;
+    info->k = h->k;
+    info->nnz = h->nnz;
+    info->format = h->format;
+    info->dtype = h->dtype;
+    info->b_row = h->b_row;
+    info->b_col = h->b_col;
+    info->task_cols = h->task_cols;
+    info->on_device = h->device >= 0 ? 1 : 0;
+    info->n_brows = h->n_brows;
+    info->n_units = h->n_units;
+    info->n_tasks = h->n_tasks;
+    info->n_zero_rows_units = h->n_zero_windows;
+    double slots = h->format == ASP_FMT_BCSR ? (double)h->n_units * h->b_row * h->b_col : (double)h->n_units * h->b_row;
+    info->fill_ratio = slots > 0 ? (double)h->nnz / slots : 0.0;
+    return ASP_OK;
+}
+
+asp_status_t asp_plan_spmm(const asp_handle_t *h, int64_t N, asp_plan_t *plan) {
+    if (!h || !plan) return fail(ASP_ERR_INVALID_ARG, "null handle or plan");
+    if (N < 1 || N >= (1ll << 31)) return fail(ASP_ERR_INVALID_ARG, "N out of range");
+    if (h->format == ASP_FMT_BCSR) {
+        BcsrPlan p = bcsr_plan(h, N, true);
+        plan->bn = p.bn;
+        plan->n_tiles = p.n_tiles;
+        plan->vectorized = p.vectorized;
+        plan->workgroups = p.workgroups;
+    } else {
+        WcsrPlan p = wcsr_plan(h, N, true);
+        plan->bn = p.bn;
+        plan->n_tiles = p.n_tiles;
+        plan->vectorized = p.vectorized;
+        plan->workgroups = p.workgroups;
+    }
+    plan->padded_n = (int64_t)plan->n_tiles * plan->bn;
+    return ASP_OK;
+}
+
+asp_status_t asp_export(const asp_handle_t *h, asp_array_t which, void *host_dst, size_t dst_bytes, size_t *needed) {
+    if (!h) return fail(ASP_ERR_INVALID_ARG, "null handle");
+    const size_t es = dtype_size(h->dtype);
+    const bool bcsr = h->format == ASP_FMT_BCSR;
+    const void *hsrc = nullptr;  // host source, when there is one
+    const void *dsrc = nullptr;  // else device source
+    size_t bytes = 0;
+    switch (which) {
+        case ASP_ARR_ROW_PTR:
+            bytes = (size_t)(h->n_brows + 1) * 4;
+            hsrc = bcsr ? (const void *)h->hb.block_row_ptr.data() : (const void *)h->hw.window_row_ptr.data();
+            dsrc = h->d_row_ptr;
+            break;
+        case ASP_ARR_COL_IDX:
+            bytes = (size_t)h->n_units * 4;
+            hsrc = bcsr ? (const void *)h->hb.block_col_idx.data() : (const void *)h->hw.window_col_idx.data();
+            dsrc = h->d_col_idx;
+            break;
+        case ASP_ARR_VALUES:
+            bytes = bcsr ? (size_t)h->n_units * h->b_row * h->b_col * es : (size_t)h->n_units * h->b_row * es;
+            hsrc = bcsr ? (const void *)h->hb.blocks.data() : (const void *)h->hw.values.data();
+            dsrc = h->d_values;
+            break;
+        case ASP_ARR_TASKS:
+            if (bcsr) return fail(ASP_ERR_INVALID_ARG, "BCSR has no task list");
+            bytes = (size_t)h->n_tasks * 16;
+            hsrc = h->hw.tasks.data();
+            dsrc = h->d_tasks;
+            break;
+        default:
+            return fail(ASP_ERR_INVALID_ARG, "unknown array id");
+    }
+    if (needed) *needed = bytes;
+    if (dst_bytes < bytes || (!host_dst && bytes > 0)) return fail(ASP_ERR_BUFFER_TOO_SMALL, "destination too small");
+    if (bytes == 0) return ASP_OK;
+    // BCSR keeps canonical arrays on the host (the device holds a permuted copy of the blocks);
+    // a WCSR device handle reads its canonical arrays back from the GPU.
+    if (bcsr || h->device < 0) {
+        std::memcpy(host_dst, hsrc, bytes);
+        return ASP_OK;
+    }
+    int cur = -1;
+    ASP_HIP_TRY(hipGetDevice(&cur));
+    if (cur != h->device) ASP_HIP_TRY(hipSetDevice(h->device));
+    hipError_t e = hipMemcpy(host_dst, dsrc, bytes, hipMemcpyDeviceToHost);
+    if (cur != h->device) (void)hipSetDevice(cur);
+    if (e != hipSuccess) return fail(ASP_ERR_HIP, std::string("hipMemcpy D2H: ") + hipGetErrorString(e));
+    return ASP_OK;
+}
+
+asp_status_t asp_destroy(asp_handle_t *h) {
+    if (!h) return ASP_OK;
+    free_device(h);
+    delete h;
+    return ASP_OK;
+}
+
+const char *asp_status_string(asp_status_t s) {
+    switch (s) {
+        case ASP_OK: return "ASP_OK";
+        case ASP_ERR_INVALID_ARG: return "ASP_ERR_INVALID_ARG";
+        case ASP_ERR_INVALID_CSR: return "ASP_ERR_INVALID_CSR";
+        case ASP_ERR_UNSUPPORTED: return "ASP_ERR_UNSUPPORTED";
+        case ASP_ERR_OUT_OF_MEMORY: return "ASP_ERR_OUT_OF_MEMORY";
+        case ASP_ERR_HIP: return "ASP_ERR_HIP";
+        case ASP_ERR_BUFFER_TOO_SMALL: return "ASP_ERR_BUFFER_TOO_SMALL";
+    }
+    return "ASP_ERR_UNKNOWN";
+}
+
+const char *asp_last_error(void) { return asp::g_last_error.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,249 @@
+// Host-side format converters of the library: CSR -> BCSR and CSR -> WCSR (paper, Section II-C) and
+// the host variant of the window sub-task list (Section III-C).  Values are bit-copied only.
+//
+// Work is spread over block-rows / windows with a shared atomic counter so that a few very long
+// windows do not serialise the conversion.
+#include <algorithm>
+#include <atomic>
+#include <cstring>
+#include <thread>
+
+#include "asp_internal.h"
+
+namespace asp {
+
+namespace {
+
+unsigned worker_count(int64_t items) {
+    unsigned hw = std::thread::hardware_concurrency();
+    if (hw == 0) hw = 1;
+    hw = std::min(hw, 32u);
+    return (unsigned)std::max<int64_t>(1, std::min<int64_t>(hw, items / 64 + 1));
+}
+
+// run fn(worker_index, first, last) over [0, n) in dynamically claimed chunks
+template <class F>
+void parallel_chunks(int64_t n, int64_t chunk, F fn) {
+    unsigned nw = worker_count(n);
+    std::atomic<int64_t> next{0};
+    auto body = [&](unsigned wi) {
+        for (;;) {
+            int64_t b = next.fetch_add(chunk);
+            if (b >= n) break;
+            fn(wi, b, std::min(n, b + chunk));
+        }
+    };
+    if (nw == 1) {
+        body(0);
+        return;
+    }
+    std::vector<std::thread> th;
+    for (unsigned w = 1; w < nw; ++w) th.emplace_back(body, w);
+    body(0);
+    for (auto &t : th) t.join();
+}
+
+}  // namespace
+
+std::string validate_csr(int64_t m, int64_t k, int64_t nnz, const int32_t *row_ptr, const int32_t *col_idx) {
+    if (row_ptr[0] != 0) return "row_ptr[0] != 0";
+    for (int64_t i = 0; i < m; ++i)
+        if (row_ptr[i + 1] < row_ptr[i]) return "row_ptr decreases at row " + std::to_string(i);
+    if (row_ptr[m] != nnz) return "row_ptr[m] != nnz";
+    std::atomic<int64_t> bad_row{-1};
+    parallel_chunks(m, 4096, [&](unsigned, int64_t b, int64_t e) {
+        for (int64_t i = b; i < e; ++i) {
+            int64_t prev = -1;
+            for (int64_t p = row_ptr[i]; p < row_ptr[i + 1]; ++p) {
+                int64_t c = col_idx[p];
+                if (c <= prev || c >= k) {
+                    int64_t expect = -1;
+                    bad_row.compare_exchange_strong(expect, i);
+                    return;
+                }
+                prev = c;
+            }
+        }
+    });
+    if (bad_row.load() >= 0)
+        return "row " + std::to_string(bad_row.load()) +
+               ": column indices must be in [0,k) and strictly ascending (no duplicates)";
+    return "";
+}
+
+// ------------------------------------------------------------------------------------------ BCSR
+void csr_to_bcsr(int64_t m, int64_t k, const int32_t *row_ptr, const int32_t *col_idx, const void *values,
+                 size_t esize, int32_t b_row, int32_t b_col, HostBcsr &out) {
+    const int64_t nbr = ceil_div(m, b_row), nbc = ceil_div(k, b_col);
+    out.block_row_ptr.assign(nbr + 1, 0);
+    unsigned nw = worker_count(nbr);
+    // stamp[w][J] == I + 1 marks "block column J already seen in block-row I" for worker w
+    std::vector<std::vector<int64_t>> stamp(nw, std::vector<int64_t>(nbc, 0));
+
+    // pass 1: number of touched block columns per block-row
+    parallel_chunks(nbr, 16, [&](unsigned wi, int64_t b, int64_t e) {
+        auto &st = stamp[wi];
+        for (int64_t I = b; I < e; ++I) {
+            int64_t r1 = std::min<int64_t>(m, (I + 1) * b_row);
+            int32_t cnt = 0;
+            for (int64_t p = row_ptr[I * b_row]; p < row_ptr[r1]; ++p) {
+                int64_t J = col_idx[p] / b_col;
+                if (st[J] != I + 1) {
+                    st[J] = I + 1;
+                    ++cnt;
+                }
+            }
+            out.block_row_ptr[I + 1] = cnt;
+        }
+    });
+    for (int64_t I = 0; I < nbr; ++I) out.block_row_ptr[I + 1] += out.block_row_ptr[I];
+    const int64_t nb = out.block_row_ptr[nbr];
+    const int64_t bsz = (int64_t)b_row * b_col;
+    out.block_col_idx.assign(nb, 0);
+    out.blocks.assign((size_t)nb * bsz * esize, 0);  // +0.0 everywhere
+
+    // pass 2: ascending block columns, then scatter the entries
+    std::vector<std::vector<int32_t>> slot(nw, std::vector<int32_t>(nbc, -1));
+    for (auto &s : stamp) std::fill(s.begin(), s.end(), 0);
+    parallel_chunks(nbr, 16, [&](unsigned wi, int64_t b, int64_t e) {
+        auto &st = stamp[wi];
+        auto &sl = slot[wi];
+        for (int64_t I = b; I < e; ++I) {
+            int64_t r0 = I * b_row, r1 = std::min<int64_t>(m, r0 + b_row);
+            int32_t *cols = out.block_col_idx.data() + out.block_row_ptr[I];
+            int32_t cnt = 0;
+            for (int64_t p = row_ptr[r0]; p < row_ptr[r1]; ++p) {
+                int32_t J = col_idx[p] / b_col;
+                if (st[J] != I + 1) {
+                    st[J] = I + 1;
+                    cols[cnt++] = J;
+                }
+            }
+            std::sort(cols, cols + cnt);
+            for (int32_t t = 0; t < cnt; ++t) sl[cols[t]] = out.block_row_ptr[I] + t;
+            for (int64_t i = r0; i < r1; ++i) {
+                for (int64_t p = row_ptr[i]; p < row_ptr[i + 1]; ++p) {
+                    int32_t c = col_idx[p];
+                    int32_t J = c / b_col;
+                    size_t dst = ((size_t)sl[J] * bsz + (size_t)(i - r0) * b_col + (size_t)(c - J * b_col)) * esize;
+                    std::memcpy(out.blocks.data() + dst, (const uint8_t *)values + (size_t)p * esize, esize);
+                }
+            }
+        }
+    });
+}
+
+// Kernel-internal order of a bf16 block: for each 16-wide k slice, for each group of 32 rows, the 64
+// lanes of a wavefront hold 8 consecutive k each (lane l: row l % 32, k offset 8 * (l / 32)), which
+// is the A/B operand layout of v_mfma_f32_32x32x16_bf16.  A pure permutation of the canonical block.
+void bcsr_pack_fragments_bf16(const HostBcsr &in, int32_t b_row, int32_t b_col, std::vector<uint8_t> &packed) {
+    const int64_t nb = (int64_t)in.block_col_idx.size();
+    const int64_t bsz = (int64_t)b_row * b_col;
+    packed.resize(in.blocks.size());
+    const uint16_t *src = (const uint16_t *)in.blocks.data();
+    uint16_t *dst = (uint16_t *)packed.data();
+    const int32_t mtiles = b_row / 32, kslices = b_col / 16;
+    parallel_chunks(nb, 4, [&](unsigned, int64_t b, int64_t e) {
+        for (int64_t q = b; q < e; ++q) {
+            const uint16_t *s = src + q * bsz;
+            uint16_t *d = dst + q * bsz;
+            for (int32_t ks = 0; ks < kslices; ++ks)
+                for (int32_t mt = 0; mt < mtiles; ++mt)
+                    for (int32_t lane = 0; lane < 64; ++lane) {
+                        int32_t row = mt * 32 + lane % 32, col = ks * 16 + 8 * (lane / 32);
+                        std::memcpy(d, s + (int64_t)row * b_col + col, 16);
+                        d += 8;
+                    }
+        }
+    });
+}
+
+// ------------------------------------------------------------------------------------------ WCSR
+namespace {
+
+// Merge the (sorted) rows of one window.  emit(t, col) is called once per distinct column in ascending
+// order with its rank t; hit(t, row_in_window, p) once per CSR entry p that sits in that column.
+template <class Emit, class Hit>
+int64_t merge_window(const int32_t *row_ptr, const int32_t *col_idx, int64_t r0, int64_t r1, int32_t k,
+                     Emit emit, Hit hit) {
+    int64_t head[64], end[64];
+    const int nr = (int)(r1 - r0);
+    for (int r = 0; r < nr; ++r) {
+        head[r] = row_ptr[r0 + r];
+        end[r] = row_ptr[r0 + r + 1];
+    }
+    int64_t t = 0;
+    for (;;) {
+        int32_t cmin = k;  // larger than any valid column
+        for (int r = 0; r < nr; ++r)
+            if (head[r] < end[r] && col_idx[head[r]] < cmin) cmin = col_idx[head[r]];
+        if (cmin == k) break;
+        emit(t, cmin);
+        for (int r = 0; r < nr; ++r)
+            if (head[r] < end[r] && col_idx[head[r]] == cmin) {
+                hit(t, r, head[r]);
+                ++head[r];
+            }
+        ++t;
+    }
+    return t;
+}
+
+}  // namespace
+
+void csr_to_wcsr(int64_t m, int64_t k, const int32_t *row_ptr, const int32_t *col_idx, const void *values,
+                 size_t esize, int32_t b_row, int32_t b_col, HostWcsr &out) {
+    const int64_t nw = ceil_div(m, b_row);
+    out.window_row_ptr.assign(nw + 1, 0);
+    parallel_chunks(nw, 64, [&](unsigned, int64_t b, int64_t e) {
+        for (int64_t w = b; w < e; ++w) {
+            int64_t r0 = w * b_row, r1 = std::min<int64_t>(m, r0 + b_row);
+            int64_t u = merge_window(row_ptr, col_idx, r0, r1, (int32_t)k, [](int64_t, int32_t) {},
+                                     [](int64_t, int, int64_t) {});
+            out.window_row_ptr[w + 1] = (int32_t)(ceil_div(u, b_col) * b_col);
+        }
+    });
+    for (int64_t w = 0; w < nw; ++w) out.window_row_ptr[w + 1] += out.window_row_ptr[w];
+    const int64_t padded = out.window_row_ptr[nw];
+    out.window_col_idx.assign(padded, -1);
+    out.values.assign((size_t)padded * b_row * esize, 0);
+    const int64_t tile = (int64_t)b_row * b_col;
+    parallel_chunks(nw, 64, [&](unsigned, int64_t b, int64_t e) {
+        for (int64_t w = b; w < e; ++w) {
+            int64_t r0 = w * b_row, r1 = std::min<int64_t>(m, r0 + b_row);
+            const int64_t p0 = out.window_row_ptr[w];
+            merge_window(
+                row_ptr, col_idx, r0, r1, (int32_t)k,
+                [&](int64_t t, int32_t col) { out.window_col_idx[p0 + t] = col; },
+                [&](int64_t t, int r, int64_t p) {
+                    int64_t pc = p0 + t;
+                    size_t dst = (size_t)((pc / b_col) * tile + (int64_t)r * b_col + pc % b_col) * esize;
+                    std::memcpy(out.values.data() + dst, (const uint8_t *)values + (size_t)p * esize, esize);
+                });
+        }
+    });
+}
+
+void wcsr_tasks_host(const std::vector<int32_t> &wrp, int32_t task_cols, std::vector<int32_t> &tasks) {
+    tasks.clear();
+    for (size_t w = 0; w + 1 < wrp.size(); ++w) {
+        const int32_t lo = wrp[w], hi = wrp[w + 1];
+        const int32_t split = (hi - lo > task_cols) ? 1 : 0;
+        for (int32_t c = lo; c < hi; c += task_cols) {
+            tasks.push_back((int32_t)w);
+            tasks.push_back(c);
+            tasks.push_back(std::min(hi, c + task_cols));
+            tasks.push_back(split);
+        }
+    }
+}
+
+void wcsr_zero_windows(const std::vector<int32_t> &wrp, int32_t task_cols, std::vector<int32_t> &zw) {
+    zw.clear();
+    for (size_t w = 0; w + 1 < wrp.size(); ++w) {
+        int32_t n = wrp[w + 1] - wrp[w];
+        if (n == 0 || n > task_cols) zw.push_back((int32_t)w);
+    }
+}
+
+}  // namespace asp

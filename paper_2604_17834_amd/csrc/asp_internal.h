@@ -1,0 +1,99 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "asyncsparse.h"
+
+namespace asp {
+
+// thread-local detail string behind asp_last_error()
+void set_error(const std::string &msg);
+asp_status_t fail(asp_status_t s, const std::string &msg);
+
+#define ASP_HIP_TRY(expr)                                                                        \
+    do {                                                                                         \
+        hipError_t e__ = (expr);                                                                 \
+        if (e__ != hipSuccess)                                                                   \
+            return ::asp::fail(e__ == hipErrorOutOfMemory ? ASP_ERR_OUT_OF_MEMORY : ASP_ERR_HIP, \
+                               std::string(#expr) + ": " + hipGetErrorString(e__));             \
+    } while (0)
+
+inline size_t dtype_size(int32_t dt) { return dt == ASP_DT_BF16 ? 2 : 4; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ---- host-side converted forms -------------------------------------------------------------
+struct HostBcsr {
+    std::vector<int32_t> block_row_ptr;  // [n_brows + 1]
+    std::vector<int32_t> block_col_idx;  // [nnz_blocks]
+    std::vector<uint8_t> blocks;         // canonical [nnz_blocks][b_row][b_col], raw bytes
+    std::vector<uint8_t> packed;         // same values in MFMA-fragment order (kernel-internal)
+};
+
+struct HostWcsr {
+    std::vector<int32_t> window_row_ptr;  // [n_windows + 1]
+    std::vector<int32_t> window_col_idx;  // [padded_cols]
+    std::vector<uint8_t> values;          // [padded_cols / b_col][b_row][b_col], raw bytes
+    std::vector<int32_t> tasks;           // [n_tasks][4]; filled on the host only in host-convert mode
+    std::vector<int32_t> zero_windows;    // windows whose C rows must be cleared (empty or split)
+};
+
+// converters (asp_convert.cpp); values are only bit-copied
+void csr_to_bcsr(int64_t m, int64_t k, const int32_t *row_ptr, const int32_t *col_idx, const void *values,
+                 size_t esize, int32_t b_row, int32_t b_col, HostBcsr &out);
+void bcsr_pack_fragments_bf16(const HostBcsr &in, int32_t b_row, int32_t b_col, std::vector<uint8_t> &packed);
+void csr_to_wcsr(int64_t m, int64_t k, const int32_t *row_ptr, const int32_t *col_idx, const void *values,
+                 size_t esize, int32_t b_row, int32_t b_col, HostWcsr &out);
+void wcsr_tasks_host(const std::vector<int32_t> &window_row_ptr, int32_t task_cols, std::vector<int32_t> &tasks);
+void wcsr_zero_windows(const std::vector<int32_t> &window_row_ptr, int32_t task_cols,
+                       std::vector<int32_t> &zero_windows);
+// returns empty string when the CSR arrays are valid, else a description of the first problem
+std::string validate_csr(int64_t m, int64_t k, int64_t nnz, const int32_t *row_ptr, const int32_t *col_idx);
+
+}  // namespace asp
+
+// ---- the opaque handle ---------------------------------------------------------------------------
+struct asp_handle {
+    int64_t m = 0, k = 0, nnz = 0;
+    int32_t format = 0, dtype = 0, b_row = 0, b_col = 0, task_cols = 0;
+    uint32_t flags = 0;
+    int device = -1;  // HIP device that owns the d_* arrays, -1 in host-convert mode
+    int64_t n_brows = 0, n_units = 0, n_tasks = 0, n_zero_windows = 0;
+
+    asp::HostBcsr hb;  // BCSR: canonical arrays stay on the host for export
+    asp::HostWcsr hw;  // WCSR: kept only in host-convert mode (device arrays are canonical)
+
+    // device arrays
+    int32_t *d_row_ptr = nullptr;   // block_row_ptr / window_row_ptr
+    int32_t *d_col_idx = nullptr;   // block_col_idx / window_col_idx
+    void *d_values = nullptr;       // BCSR: fragment-packed blocks; WCSR: canonical tiles
+    int32_t *d_tasks = nullptr;     // WCSR tasks [n_tasks][4]
+    int32_t *d_zero_windows = nullptr;
+};
+
+namespace asp {
+// kernels' host launchers (asp_bcsr.hip / asp_wcsr.hip)
+struct BcsrPlan {
+    int32_t bn;
+    int32_t n_tiles;
+    int32_t vectorized;
+    int64_t workgroups;
+};
+BcsrPlan bcsr_plan(const asp_handle *h, int64_t N, bool aligned);
+asp_status_t bcsr_spmm_launch(const asp_handle *h, const void *B, void *C, int64_t N, hipStream_t stream);
+
+struct WcsrPlan {
+    int32_t bn;
+    int32_t n_tiles;
+    int32_t vectorized;
+    int64_t workgroups;
+};
+WcsrPlan wcsr_plan(const asp_handle *h, int64_t N, bool aligned);
+asp_status_t wcsr_spmm_launch(const asp_handle *h, const void *B, void *C, int64_t N, hipStream_t stream);
+// GPU task partition: fills h->d_tasks / h->n_tasks from h->d_row_ptr (wavefront scans)
+asp_status_t wcsr_build_tasks_device(asp_handle *h, hipStream_t stream);
+}  // namespace asp

@@ -1,0 +1,289 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, element by element.
+
+Tolerances (stated by the benchmark spec, written here):
+  bf16 inputs, fp32 accumulation, bf16 output:  |C - C_ref| <= 1e-2 * S + 1e-5
+  fp32 inputs and output:                       |C - C_ref| <= 1e-5 * S
+with S = (|A| x |B|)_ij from the oracle.  Format arrays must be bit-exact.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2604_17834_amd import binding as asp
+from paper_2604_17834_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _dev_in(x: np.ndarray):
+    if x.dtype == np.uint16:
+        return torch.from_numpy(x.view(np.int16)).cuda()
+    return torch.from_numpy(x).cuda()
+
+
+def gpu_spmm(a: synth.Csr, fmt, b_row, b_col, B: np.ndarray, task_cols=0, handle=None, misalign=False):
+    """One asp_create_from_csr + asp_spmm; returns C as numpy (uint16 bits or float32)."""
+    own = handle is None
+    if own:
+        handle = asp.asp_create_from_csr(fmt, a.dtype, b_row, b_col, a.m, a.k, a.row_ptr, a.col_idx, a.values,
+                                         task_cols=task_cols)
+    try:
+        N = B.shape[1]
+        tdt = torch.int16 if a.dtype == "bf16" else torch.float32
+        if misalign:  # shift both operands off 16-byte alignment by one element
+            Bfull = torch.empty(B.size + 1, dtype=tdt, device="cuda")
+            Bd = Bfull[1:].view(B.shape)
+            Bd.copy_(_dev_in(np.ascontiguousarray(B)))
+            Cfull = torch.empty(a.m * N + 1, dtype=tdt, device="cuda")
+            Cd = Cfull[1:].view(a.m, N)
+        else:
+            Bd = _dev_in(np.ascontiguousarray(B))
+            Cd = torch.empty((a.m, N), dtype=tdt, device="cuda")
+        # poison C: every element must be overwritten (bf16 0x7FC1 / fp32 NaN)
+        if a.dtype == "bf16":
+            Cd.fill_(0x7FC1)
+        else:
+            Cd.fill_(float("nan"))
+        stream = torch.cuda.current_stream().cuda_stream
+        asp.asp_spmm(handle, Bd.data_ptr(), Cd.data_ptr(), N, stream)
+        torch.cuda.synchronize()
+        out = Cd.cpu().numpy()
+        return out.view(np.uint16) if a.dtype == "bf16" else out
+    finally:
+        if own:
+            asp.asp_destroy(handle)
+
+
+def check_against_oracle(a: synth.Csr, B: np.ndarray, C: np.ndarray, cols=None):
+    Bs = B if cols is None else np.ascontiguousarray(B[:, cols])
+    Cs = C if cols is None else C[:, cols]
+    ref, S = oracle.spmm(a.m, a.k, a.row_ptr, a.col_idx, a.values, a.dtype, Bs)
+    got = synth.to_f64(Cs, a.dtype)
+    assert np.isfinite(got).all(), "unwritten or non-finite output"
+    err = np.abs(got - ref)
+    bound = 1e-2 * S + 1e-5 if a.dtype == "bf16" else 1e-5 * S
+    worst = np.unravel_index(np.argmax(err - bound), err.shape)
+    assert (err <= bound).all(), "worst at %s: got %r ref %r bound %r" % (worst, got[worst], ref[worst], bound[worst])
+    return float((err / np.maximum(bound, 1e-300)).max())
+
+
+# ------------------------------------------------------------------ BCSR
+@pytest.mark.parametrize("b", [32, 64, 128])
+@pytest.mark.parametrize("m,k,N,sparsity", [
+    (256, 256, 256, 0.5),     # several tiles
+    (384, 512, 64, 0.7),
+    (300, 200, 128, 0.6),     # ragged M and K (last block row / column partly outside)
+    (512, 384, 320, 0.8),     # N = 5 x 64: narrow tile chosen by the width rule
+    (256, 256, 200, 0.5),     # masked N tail, 16-byte path (200 % 8 == 0)
+    (160, 288, 100, 0.5),     # N % 8 != 0: element-wise path
+    (128, 128, 8, 0.0),
+    (128, 256, 1, 0.3),
+])
+def test_bcsr_parity(b, m, k, N, sparsity):
+    a = synth.block_sparse_bernoulli(m, k, b, b, sparsity, seed=100 + b + N)
+    B = synth.dense_normal(k, N, "bf16", seed=7 + N)
+    C = gpu_spmm(a, "bcsr", b, b, B)
+    check_against_oracle(a, B, C)
+
+
+@pytest.mark.parametrize("b", [32, 64, 128])
+def test_bcsr_scattered_entries_and_empty_block_rows(b):
+    # unstructured entries: blocks are mostly zero padding; 30 % of rows empty => empty block-rows exist
+    a = synth.random_csr(520, 390, 0.002, seed=b, dtype="bf16", empty_row_frac=0.3, dist="normal")
+    B = synth.dense_normal(a.k, 136, "bf16", seed=1)
+    C = gpu_spmm(a, "bcsr", b, b, B)
+    check_against_oracle(a, B, C)
+    empty = np.diff(a.row_ptr) == 0
+    assert not C[empty].any()          # exactly +0
+
+
+def test_bcsr_nnz_zero():
+    a = synth.random_csr(100, 100, 0.0, seed=1, dtype="bf16")
+    B = synth.dense_normal(100, 64, "bf16", seed=2)
+    assert not gpu_spmm(a, "bcsr", 64, 64, B).any()
+
+
+@pytest.mark.parametrize("b", [32, 64, 128])
+def test_bcsr_times_identity_is_A_bit_exact(b):
+    # products with 1.0 and sums with 0.0 are exact: the result must be A's bits, whatever the layout
+    a = synth.random_csr(300, 256, 0.05, seed=10 + b, dtype="bf16", dist="normal")
+    C = gpu_spmm(a, "bcsr", b, b, synth.dense_identity(a.k, "bf16"))
+    dense = np.zeros((a.m, a.k), np.uint16)
+    for i in range(a.m):
+        dense[i, a.col_idx[a.row_ptr[i]:a.row_ptr[i + 1]]] = a.values[a.row_ptr[i]:a.row_ptr[i + 1]]
+    assert np.array_equal(C, dense)
+
+
+def test_bcsr_column_slice_and_rerun_bitwise():
+    a = synth.block_sparse_geometric(512, 512, 64, 64, 0.7, seed=3)
+    B = synth.dense_normal(a.k, 512, "bf16", seed=4)
+    h = asp.asp_create_from_csr("bcsr", "bf16", 64, 64, a.m, a.k, a.row_ptr, a.col_idx, a.values)
+    try:
+        C1 = gpu_spmm(a, "bcsr", 64, 64, B, handle=h)
+        C2 = gpu_spmm(a, "bcsr", 64, 64, B, handle=h)
+        assert np.array_equal(C1, C2)
+        Cs = gpu_spmm(a, "bcsr", 64, 64, np.ascontiguousarray(B[:, 128:384]), handle=h)
+        assert np.array_equal(C1[:, 128:384], Cs)
+    finally:
+        asp.asp_destroy(h)
+
+
+def test_bcsr_misaligned_pointers_take_elementwise_path():
+    a = synth.block_sparse_bernoulli(256, 256, 64, 64, 0.5, seed=5)
+    B = synth.dense_normal(a.k, 64, "bf16", seed=6)
+    C = gpu_spmm(a, "bcsr", 64, 64, B, misalign=True)
+    check_against_oracle(a, B, C)
+
+
+def test_bcsr_config1_full():
+    a, fmt, br, bc, N, dt, seedB = synth.workload("bcsr_small")
+    B = synth.dense_normal(a.k, N, dt, seedB)
+    C = gpu_spmm(a, fmt, br, bc, B)
+    check_against_oracle(a, B, C)
+
+
+def _sample_columns(N, tile, rng):
+    cols = list(range(0, 32)) + list(range(N - 32, N))
+    for _ in range(2):
+        s = int(rng.integers(1, N // tile - 1)) * tile + int(rng.integers(0, tile - 32))
+        cols += list(range(s, s + 32))
+    return np.array(sorted(set(cols)))
+
+
+@pytest.mark.parametrize("name", ["bcsr_gate_proj", "bcsr_down_proj"])
+def test_bcsr_config2_full_size_sampled_columns(name):
+    # full benchmark shape on the GPU; every row checked on 128 sampled columns (a column of C
+    # depends on the same column of B only, so the slice is an exact sub-problem for the oracle)
+    a, fmt, br, bc, N, dt, seedB = synth.workload(name)
+    B = synth.dense_normal(a.k, N, dt, seedB)
+    C = gpu_spmm(a, fmt, br, bc, B)
+    cols = _sample_columns(N, 256, np.random.default_rng(1))
+    check_against_oracle(a, B, C, cols)
+    # block-rows without blocks give exact zeros over the full width
+    h = asp.asp_create_from_csr(fmt, dt, br, bc, a.m, a.k, a.row_ptr, a.col_idx, a.values,
+                                flags=asp.ASP_FLAG_HOST_CONVERT_ONLY)
+    brp = asp.asp_export(h, asp.ASP_ARR_ROW_PTR)
+    asp.asp_destroy(h)
+    for I in np.nonzero(np.diff(brp) == 0)[0]:
+        assert not C[I * br:(I + 1) * br].any()
+
+
+@pytest.mark.parametrize("b,sparsity", [(32, 0.9), (64, 0.75), (128, 0.95)])
+def test_bcsr_geometric_rows_sampled(b, sparsity):
+    # config-5 style: per-block-row length variance; reduced width so the oracle finishes in seconds
+    a = synth.block_sparse_geometric(2048, 2048, b, b, sparsity, seed=50 + b)
+    B = synth.dense_normal(a.k, 1024, "bf16", seed=51)
+    C = gpu_spmm(a, "bcsr", b, b, B)
+    check_against_oracle(a, B, C, _sample_columns(1024, 256, np.random.default_rng(2)))
+
+
+# ------------------------------------------------------------------ WCSR
+@pytest.mark.parametrize("b_row", [16, 32, 64])
+@pytest.mark.parametrize("m,k,N,density,task_cols", [
+    (256, 300, 128, 0.05, 0),
+    (200, 512, 64, 0.10, 16),      # splits: atomics + cleared rows
+    (333, 257, 256, 0.03, 8),      # ragged last window, every window split
+    (128, 128, 192, 0.10, 32),     # N = 3 x 64
+    (100, 90, 100, 0.10, 16),      # masked N tail, 16-byte path
+    (77, 140, 50, 0.15, 24),       # N % 4 != 0: element-wise path
+    (64, 64, 4, 0.2, 0),
+    (64, 64, 1, 0.2, 8),
+])
+def test_wcsr_parity(b_row, m, k, N, density, task_cols):
+    a = synth.random_csr(m, k, density, seed=200 + m + N, dtype="f32", empty_row_frac=0.15)
+    B = synth.dense_normal(k, N, "f32", seed=9 + N)
+    C = gpu_spmm(a, "wcsr", b_row, 8, B, task_cols=task_cols)
+    check_against_oracle(a, B, C)
+    empty = np.diff(a.row_ptr) == 0
+    assert not C[empty].any()
+
+
+@pytest.mark.parametrize("b_row", [16, 32, 64])
+def test_wcsr_times_identity_is_A_bit_exact(b_row):
+    a = synth.random_csr(150, 128, 0.08, seed=20 + b_row, dtype="f32")
+    C = gpu_spmm(a, "wcsr", b_row, 8, synth.dense_identity(a.k, "f32"), task_cols=16)
+    dense = np.zeros((a.m, a.k), np.float32)
+    for i in range(a.m):
+        dense[i, a.col_idx[a.row_ptr[i]:a.row_ptr[i + 1]]] = a.values[a.row_ptr[i]:a.row_ptr[i + 1]]
+    assert np.array_equal(C, dense)
+
+
+def test_wcsr_empty_windows_and_nnz_zero():
+    a = synth.random_csr(256, 200, 0.0, seed=1, dtype="f32")
+    assert not gpu_spmm(a, "wcsr", 16, 8, synth.dense_normal(200, 64, "f32", 2)).any()
+    a = synth.random_csr(256, 200, 0.05, seed=3, dtype="f32", empty_row_frac=0.9)  # many windows without columns
+    B = synth.dense_normal(200, 128, "f32", 4)
+    check_against_oracle(a, B, gpu_spmm(a, "wcsr", 16, 8, B))
+
+
+def test_wcsr_unsplit_is_bitwise_reproducible_and_slice_consistent():
+    a = synth.zipf_graph(4096, 4096, 16 * 4096, seed=8, cap=400)
+    B = synth.dense_normal(a.k, 256, "f32", seed=9)
+    h = asp.asp_create_from_csr("wcsr", "f32", 16, 8, a.m, a.k, a.row_ptr, a.col_idx, a.values, task_cols=1 << 20)
+    try:
+        assert asp.asp_get_info(h).n_zero_rows_units == np.count_nonzero(
+            np.diff(asp.asp_export(h, asp.ASP_ARR_ROW_PTR)) == 0)
+        C1 = gpu_spmm(a, "wcsr", 16, 8, B, handle=h)
+        C2 = gpu_spmm(a, "wcsr", 16, 8, B, handle=h)
+        assert np.array_equal(C1, C2)
+        Cs = gpu_spmm(a, "wcsr", 16, 8, np.ascontiguousarray(B[:, 64:192]), handle=h)
+        assert np.array_equal(C1[:, 64:192], Cs)
+    finally:
+        asp.asp_destroy(h)
+
+
+def test_wcsr_task_cols_does_not_change_result_beyond_tolerance():
+    a = synth.zipf_graph(2048, 2048, 16 * 2048, seed=11, cap=900)
+    B = synth.dense_normal(a.k, 128, "f32", seed=12)
+    for tc in (8, 64, 512):
+        check_against_oracle(a, B, gpu_spmm(a, "wcsr", 16, 8, B, task_cols=tc))
+
+
+@pytest.mark.parametrize("b_row,task_cols", [(16, 64), (32, 8), (64, 512)])
+def test_wcsr_device_arrays_and_gpu_task_partition_bit_exact(b_row, task_cols):
+    # the task list of a device handle comes from the wavefront-scan kernels
+    a = synth.zipf_graph(40000, 40000, 12 * 40000, seed=13, cap=5000)
+    h = asp.asp_create_from_csr("wcsr", "f32", b_row, 8, a.m, a.k, a.row_ptr, a.col_idx, a.values, task_cols=task_cols)
+    try:
+        wrp, wci, vals = oracle.to_wcsr(a.m, a.k, a.row_ptr, a.col_idx, a.values, "f32", b_row, 8)
+        assert asp.asp_get_info(h).on_device == 1
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_ROW_PTR), wrp)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_COL_IDX), wci)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_VALUES).view(np.uint32), vals.view(np.uint32))
+        tasks = oracle.wcsr_tasks(wrp, task_cols)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_TASKS), tasks)
+        assert asp.asp_get_info(h).n_tasks == len(tasks)
+    finally:
+        asp.asp_destroy(h)
+
+
+def test_bcsr_device_handle_exports_canonical_arrays():
+    a = synth.block_sparse_bernoulli(512, 640, 128, 128, 0.6, seed=14)
+    h = asp.asp_create_from_csr("bcsr", "bf16", 128, 128, a.m, a.k, a.row_ptr, a.col_idx, a.values)
+    try:
+        brp, bci, blocks = oracle.to_bcsr(a.m, a.k, a.row_ptr, a.col_idx, a.values, "bf16", 128, 128)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_ROW_PTR), brp)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_COL_IDX), bci)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_VALUES), blocks)
+    finally:
+        asp.asp_destroy(h)
+
+
+def test_wcsr_config3_full_size():
+    # full irregular workload; the oracle does all 2^20 x 128 outputs
+    a, fmt, br, bc, N, dt, seedB = synth.workload("wcsr_zipf")
+    B = synth.dense_normal(a.k, N, dt, seedB)
+    C = gpu_spmm(a, fmt, br, bc, B)
+    check_against_oracle(a, B, C)
+
+
+def test_wcsr_config4_reduced_band_plus_dense_rows():
+    # band + long rows at 1/8 scale (long rows still span hundreds of tasks); N = 64 and 256
+    a, fmt, br, bc, _, dt, seedB = synth.workload("wcsr_band_dense_rows", scale=0.125)
+    for N in (64, 256):
+        B = synth.dense_normal(a.k, N, dt, seedB + N)
+        C = gpu_spmm(a, fmt, br, bc, B)
+        cols = None if N == 64 else np.arange(96, 160)
+        check_against_oracle(a, B, C, cols)

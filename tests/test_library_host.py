@@ -1,0 +1,170 @@
+"""Host-side checks of the C-ABI library (no GPU): symbols, argument errors, and the library's own
+format converters bit for bit against the oracle's (host-convert mode makes no HIP call)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2604_17834_amd import binding as asp
+from paper_2604_17834_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HOST = asp.ASP_FLAG_HOST_CONVERT_ONLY
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "asyncsparse.h")).read()
+    declared = set(re.findall(r"\b(asp_[a-z_]+)\s*\(", header))
+    assert declared == set(asp.EXPORTED_SYMBOLS)
+    L = asp.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_status_strings():
+    assert asp.asp_status_string(0) == "ASP_OK"
+    assert asp.asp_status_string(2) == "ASP_ERR_INVALID_CSR"
+    assert asp.asp_status_string(99) == "ASP_ERR_UNKNOWN"
+
+
+def _create_status(fmt, dtype, br, bc, m, k, rp, ci, va, task_cols=0, flags=HOST):
+    st, h = asp.asp_create_from_csr(fmt, dtype, br, bc, m, k, rp, ci, va, task_cols, flags, check=False)
+    if h:
+        asp.asp_destroy(h)
+    return st
+
+
+def test_argument_and_csr_errors():
+    rp = np.array([0, 1, 2], np.int32)
+    ci = np.array([0, 1], np.int32)
+    bf = np.array([1, 2], np.uint16)
+    f32 = np.array([1, 2], np.float32)
+    ok = _create_status("bcsr", "bf16", 32, 32, 2, 2, rp, ci, bf)
+    assert ok == asp.ASP_OK
+    assert _create_status("bcsr", "bf16", 48, 48, 2, 2, rp, ci, bf) == asp.ASP_ERR_UNSUPPORTED
+    assert _create_status("bcsr", "bf16", 64, 32, 2, 2, rp, ci, bf) == asp.ASP_ERR_UNSUPPORTED
+    assert _create_status("bcsr", "f32", 64, 64, 2, 2, rp, ci, f32) == asp.ASP_ERR_UNSUPPORTED
+    assert _create_status("wcsr", "f32", 16, 4, 2, 2, rp, ci, f32) == asp.ASP_ERR_UNSUPPORTED
+    assert _create_status("wcsr", "f32", 16, 8, 2, 2, rp, ci, f32, task_cols=12) == asp.ASP_ERR_INVALID_ARG
+    assert _create_status(7, "f32", 16, 8, 2, 2, rp, ci, f32) == asp.ASP_ERR_INVALID_ARG
+    assert _create_status("wcsr", "f32", 16, 8, 0, 2, rp, ci, f32) == asp.ASP_ERR_INVALID_ARG
+    assert _create_status("wcsr", "f32", 16, 8, 2, 2, rp, ci, f32, flags=HOST | 8) == asp.ASP_ERR_INVALID_ARG
+    # broken CSR
+    bad = asp.ASP_ERR_INVALID_CSR
+    assert _create_status("wcsr", "f32", 16, 8, 2, 2, np.array([1, 1, 2], np.int32), ci, f32) == bad
+    assert _create_status("wcsr", "f32", 16, 8, 2, 2, np.array([0, 2, 1], np.int32), ci, f32) == bad
+    assert _create_status("wcsr", "f32", 16, 8, 2, 2, np.array([0, 1, 1], np.int32), ci, f32) == bad   # row_ptr[m] != nnz
+    assert _create_status("wcsr", "f32", 16, 8, 2, 2, rp, np.array([0, 2], np.int32), f32) == bad       # col >= k
+    assert _create_status("wcsr", "f32", 16, 8, 2, 2, rp, np.array([-1, 0], np.int32), f32) == bad
+    rp2 = np.array([0, 2, 2], np.int32)
+    assert _create_status("wcsr", "f32", 16, 8, 2, 2, rp2, np.array([1, 0], np.int32), f32) == bad      # unsorted
+    assert _create_status("wcsr", "f32", 16, 8, 2, 2, rp2, np.array([1, 1], np.int32), f32) == bad      # duplicate
+    assert "ascending" in asp.asp_last_error()
+    # null handle paths
+    assert asp.lib().asp_get_info(None, None) == asp.ASP_ERR_INVALID_ARG
+    assert asp.lib().asp_spmm(None, None, None, 4, None) == asp.ASP_ERR_INVALID_ARG
+    assert asp.lib().asp_destroy(None) == asp.ASP_OK
+
+
+def test_host_handle_refuses_spmm_and_small_export_buffer():
+    a = synth.random_csr(40, 40, 0.1, 3, "f32")
+    h = asp.asp_create_from_csr("wcsr", "f32", 16, 8, a.m, a.k, a.row_ptr, a.col_idx, a.values, flags=HOST)
+    try:
+        assert asp.asp_get_info(h).on_device == 0
+        assert asp.lib().asp_spmm(h, 16, 32, 8, None) == asp.ASP_ERR_UNSUPPORTED
+        assert asp.lib().asp_spmm(h, 16, 32, 0, None) == asp.ASP_ERR_INVALID_ARG
+        need = ctypes.c_size_t()
+        buf = np.zeros(1, np.int32)
+        st = asp.lib().asp_export(h, asp.ASP_ARR_COL_IDX, buf.ctypes.data_as(ctypes.c_void_p), 4, ctypes.byref(need))
+        assert st == asp.ASP_ERR_BUFFER_TOO_SMALL and need.value == 4 * asp.asp_get_info(h).n_units
+    finally:
+        asp.asp_destroy(h)
+
+
+@pytest.mark.parametrize("m,k,br,density", [(64, 64, 32, 0.05), (200, 130, 32, 0.02), (129, 257, 64, 0.01),
+                                            (300, 300, 128, 0.005), (31, 33, 32, 0.3), (128, 128, 64, 0.0)])
+def test_bcsr_converter_bit_exact_vs_oracle(m, k, br, density):
+    a = synth.random_csr(m, k, density, 5, "bf16", empty_row_frac=0.2, dist="normal")
+    h = asp.asp_create_from_csr("bcsr", "bf16", br, br, m, k, a.row_ptr, a.col_idx, a.values, flags=HOST)
+    try:
+        brp, bci, blocks = oracle.to_bcsr(m, k, a.row_ptr, a.col_idx, a.values, "bf16", br, br)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_ROW_PTR), brp)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_COL_IDX), bci)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_VALUES), blocks)
+        info = asp.asp_get_info(h)
+        assert (info.n_brows, info.n_units, info.nnz) == (len(brp) - 1, len(bci), a.nnz)
+        assert info.fill_ratio == oracle.fill_ratio(a.nnz, len(bci), br, br)
+    finally:
+        asp.asp_destroy(h)
+
+
+def test_bcsr_converter_block_mask_workload():
+    a = synth.block_sparse_geometric(512, 768, 64, 64, 0.8, seed=9)
+    h = asp.asp_create_from_csr("bcsr", "bf16", 64, 64, a.m, a.k, a.row_ptr, a.col_idx, a.values, flags=HOST)
+    try:
+        brp, bci, blocks = oracle.to_bcsr(a.m, a.k, a.row_ptr, a.col_idx, a.values, "bf16", 64, 64)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_ROW_PTR), brp)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_COL_IDX), bci)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_VALUES), blocks)
+        assert asp.asp_get_info(h).fill_ratio == 1.0
+    finally:
+        asp.asp_destroy(h)
+
+
+@pytest.mark.parametrize("m,k,br,density,task_cols", [(64, 64, 16, 0.05, 0), (200, 130, 16, 0.1, 16),
+                                                      (129, 257, 32, 0.05, 8), (300, 300, 64, 0.02, 64),
+                                                      (15, 33, 16, 0.5, 8), (128, 128, 16, 0.0, 0)])
+def test_wcsr_converter_and_tasks_bit_exact_vs_oracle(m, k, br, density, task_cols):
+    a = synth.random_csr(m, k, density, 6, "f32", empty_row_frac=0.2)
+    h = asp.asp_create_from_csr("wcsr", "f32", br, 8, m, k, a.row_ptr, a.col_idx, a.values, task_cols=task_cols,
+                                flags=HOST)
+    try:
+        wrp, wci, vals = oracle.to_wcsr(m, k, a.row_ptr, a.col_idx, a.values, "f32", br, 8)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_ROW_PTR), wrp)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_COL_IDX), wci)
+        got = asp.asp_export(h, asp.ASP_ARR_VALUES)
+        assert np.array_equal(got.view(np.uint32), vals.view(np.uint32))
+        tc = task_cols or 512
+        tasks = oracle.wcsr_tasks(wrp, tc)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_TASKS), tasks)
+        info = asp.asp_get_info(h)
+        assert (info.n_tasks, info.task_cols, info.n_units) == (len(tasks), tc, len(wci))
+        widths = np.diff(wrp)
+        assert info.n_zero_rows_units == np.count_nonzero((widths == 0) | (widths > tc))
+    finally:
+        asp.asp_destroy(h)
+
+
+def test_wcsr_converter_irregular_workloads():
+    for a in (synth.zipf_graph(2048, 2048, 16 * 2048, seed=3, cap=700),
+              synth.banded_plus_dense_rows(4096, seed=4, n_dense_rows=4, dense_row_nnz=1500)):
+        h = asp.asp_create_from_csr("wcsr", "f32", 16, 8, a.m, a.k, a.row_ptr, a.col_idx, a.values, task_cols=64,
+                                    flags=HOST)
+        try:
+            wrp, wci, vals = oracle.to_wcsr(a.m, a.k, a.row_ptr, a.col_idx, a.values, "f32", 16, 8)
+            assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_ROW_PTR), wrp)
+            assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_COL_IDX), wci)
+            assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_VALUES).view(np.uint32), vals.view(np.uint32))
+            assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_TASKS), oracle.wcsr_tasks(wrp, 64))
+        finally:
+            asp.asp_destroy(h)
+
+
+def test_plan_follows_tile_width_rule():
+    a = synth.block_sparse_bernoulli(256, 256, 128, 128, 0.5, 1)
+    h = asp.asp_create_from_csr("bcsr", "bf16", 128, 128, a.m, a.k, a.row_ptr, a.col_idx, a.values, flags=HOST)
+    try:
+        for N in (64, 128, 192, 256, 320, 1024, 16384, 100, 72, 1):
+            p = asp.asp_plan_spmm(h, N)
+            if N % 8 == 0:
+                assert p.vectorized == 1
+                assert p.bn == oracle.choose_bn(N, [64, 128, 256])
+            else:
+                assert p.vectorized == 0 and p.bn == 64
+            assert p.n_tiles == -(-N // p.bn) and p.padded_n == oracle.padded_width(N, p.bn)
+            assert p.workgroups == 2 * p.n_tiles
+    finally:
+        asp.asp_destroy(h)
