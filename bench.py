@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the SpMM hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps 100] [--warmup 10] [--workload bcsr_gate_proj] [--also wcsr_zipf]
+
+A step is one asp_spmm call (C-initialisation, tile-width choice and the SpMM kernel) on a handle whose
+format conversion and task partition were done once up front, with A, B and C resident in HBM -- the
+protocol of the paper's Section IV (10 warm-up + 100 timed launches, throughput 2*nnz*N/t with nnz of
+the original matrix).  The conversion time is reported separately in the same JSON line.
+
+Prints ONE JSON line.  `value` uses the wall-clock time of the K timed steps; `roofline.achieved` uses the
+average kernel time measured with events on the launch stream.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+# the paper's numbers (NVIDIA H100, other hardware: context only)
+PAPER_CONTEXT = {
+    "hardware": "NVIDIA H100",
+    "wcsr_speedup_over_accspmm": 1.47, "wcsr_speedup_over_cusparse": 6.24,
+    "bcsr_end_to_end_prefill_speedup_at_90pct": 2.66,
+    "bcsr_gate_proj_kernel_speedup_over_dense_90pct_n16384": 1.92,
+}
+
+
+def _measured_traffic(workload):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if one exists for this workload."""
+    p = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(p):
+        try:
+            return json.load(open(p)).get(workload, {}).get("bytes_per_launch")
+        except Exception:
+            return None
+    return None
+
+
+def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
+    import numpy as np
+
+    t0 = time.time()
+    a, fmt, b_row, b_col, N, dt, seedB = synth.workload(name)
+    B = synth.dense_normal(a.k, N, dt, seedB)
+    t_gen = time.time() - t0
+
+    stream = torch.cuda.current_stream().cuda_stream
+    t0 = time.time()
+    h = asp.asp_create_from_csr(fmt, dt, b_row, b_col, a.m, a.k, a.row_ptr, a.col_idx, a.values)
+    t_convert = time.time() - t0
+    info = asp.asp_get_info(h)
+    plan = asp.asp_plan_spmm(h, N)
+
+    if dt == "bf16":
+        Bd = torch.from_numpy(B.view(np.int16)).cuda()
+        Cd = torch.empty((a.m, N), dtype=torch.int16, device="cuda")
+    else:
+        Bd = torch.from_numpy(B).cuda()
+        Cd = torch.empty((a.m, N), dtype=torch.float32, device="cuda")
+    bp, cp = Bd.data_ptr(), Cd.data_ptr()
+
+    for _ in range(warmup):
+        asp.asp_spmm(h, bp, cp, N, stream)
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    ends = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    torch.cuda.synchronize()
+    w0 = time.perf_counter()
+    for i in range(steps):
+        starts[i].record()
+        asp.asp_spmm(h, bp, cp, N, stream)
+        ends[i].record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - w0) * 1e3 / steps
+    per = np.array([s.elapsed_time(e) for s, e in zip(starts, ends)])
+    kern_ms = float(per.mean())
+
+    flops_eff = 2.0 * a.nnz * N
+    esz = 2 if dt == "bf16" else 4
+    if fmt == "bcsr":
+        # work per stored block: 2*b_row*b_col*N flop (Section II-C: zeros inside blocks are computed)
+        flops_alg = 2.0 * info.n_units * b_row * b_col * N
+        bytes_alg = info.n_units * b_row * b_col * esz + a.k * N * esz + a.m * N * esz
+        roof = {"bound": "mfma", "achieved": flops_alg / (kern_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s"}
+        extra = {"stored_blocks": int(info.n_units), "algorithmic_bytes": int(bytes_alg),
+                 "hbm_floor_ms": bytes_alg / (PEAK_HBM_GBS * 1e9) * 1e3,
+                 "mfma_floor_ms": flops_alg / (PEAK_BF16_TFLOPS * 1e12) * 1e3}
+    else:
+        wci = asp.asp_export(h, asp.ASP_ARR_COL_IDX)
+        tasks = asp.asp_export(h, asp.ASP_ARR_TASKS)
+        real_cols = int((wci >= 0).sum())
+        split_windows = int(len(np.unique(tasks[tasks[:, 3] != 0, 0]))) if len(tasks) else 0
+        # per packed column: b_row values + 1 index of A, one gathered B row; per window one C tile
+        # (split windows: cleared, then read-modify-written by every task -- counted as 2 extra passes)
+        bytes_alg = (info.n_units * (b_row * 4 + 4) + real_cols * N * 4 + a.m * N * 4
+                     + 2 * split_windows * b_row * N * 4)
+        roof = {"bound": "hbm", "achieved": bytes_alg / (kern_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
+        extra = {"packed_cols": int(info.n_units), "real_cols": real_cols, "tasks": int(info.n_tasks),
+                 "split_windows": split_windows, "algorithmic_bytes": int(bytes_alg),
+                 "mfma_flops_padded": 2.0 * info.n_units * b_row * N}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = _measured_traffic(name)
+    roof["kernel_ms_avg"] = kern_ms
+    roof["kernel_ms_median"] = float(np.median(per))
+
+    res = {
+        "workload": name, "format": fmt, "b_row": b_row, "b_col": b_col, "m": a.m, "k": a.k, "N": N, "nnz": a.nnz,
+        "fill_ratio": info.fill_ratio, "bn": plan.bn, "workgroups": int(plan.workgroups),
+        "value": flops_eff / (wall_ms * 1e-3) / 1e9, "ms_per_step": wall_ms, "roofline": roof,
+        "convert_s": t_convert, "generate_s": t_gen, **extra,
+    }
+
+    if with_cpu_baseline:
+        import oracle
+        # bounded sample: the oracle on a slice of B's columns (column j of C needs column j of B only)
+        probe = min(N, 16)
+        t0 = time.perf_counter()
+        oracle.spmm(a.m, a.k, a.row_ptr, a.col_idx, a.values, dt, np.ascontiguousarray(B[:, :probe]))
+        tp = time.perf_counter() - t0
+        ncols = int(max(probe, min(N, 15.0 / max(tp / probe, 1e-9))))
+        ncols = max(16, ncols // 16 * 16) if N >= 16 else N
+        Bs = np.ascontiguousarray(B[:, :ncols])
+        t0 = time.perf_counter()
+        ref, S = oracle.spmm(a.m, a.k, a.row_ptr, a.col_idx, a.values, dt, Bs)
+        tc = time.perf_counter() - t0
+        got = Cd[:, :ncols].cpu().numpy()
+        got = synth.to_f64(got.view(np.uint16), "bf16") if dt == "bf16" else got.astype(np.float64)
+        bound = 1e-2 * S + 1e-5 if dt == "bf16" else 1e-5 * S
+        ok = bool(np.isfinite(got).all() and (np.abs(got - ref) <= bound).all())
+        res["cpu_baseline"] = {"value": 2.0 * a.nnz * ncols / tc / 1e9, "unit": "GFLOP/s", "cores": oracle.num_threads(),
+                               "kind": "oracle", "seconds": tc,
+                               "sample": "first %d of %d columns of B, all %d rows (fp64 CSR oracle, includes the "
+                                         "|A||B| bound pass)" % (ncols, N, a.m),
+                               "gpu_matches_oracle_on_sample": ok}
+    asp.asp_destroy(h)
+    del Bd, Cd
+    torch.cuda.empty_cache()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="bcsr_gate_proj")
+    ap.add_argument("--also", default="wcsr_zipf", help="comma list of further workloads reported under 'also' ('' = none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU by design (one MI355X, no collectives); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2604_17834_amd import binding as asp
+    from paper_2604_17834_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the SpMM path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    asp.lib()  # raises when the HIP library has not been built
+
+    main_res = run_workload(args.workload, args.steps, args.warmup, torch, asp, synth, not args.no_cpu_baseline)
+    also = []
+    for name in [s for s in args.also.split(",") if s and s != args.workload]:
+        also.append(run_workload(name, args.steps, args.warmup, torch, asp, synth, not args.no_cpu_baseline))
+
+    line = {
+        "metric": "effective SpMM GFLOP/s (2*nnz*N/t), BCSR gate_proj 18944x3584 bf16 128x128 blocks 90% sparse, N=16384"
+                  if args.workload == "bcsr_gate_proj" else "effective SpMM GFLOP/s (2*nnz*N/t)",
+        "value": main_res["value"], "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if main_res["format"] == "bcsr" else "f32", "data": "synthetic",
+        "config": {"workload": args.workload, **{k: main_res[k] for k in
+                                                   ("format", "b_row", "b_col", "m", "k", "N", "nnz", "bn", "workgroups")}},
+        "roofline": main_res["roofline"],
+        "cpu_baseline": main_res.get("cpu_baseline"),
+        "detail": {k: v for k, v in main_res.items() if k not in ("roofline", "cpu_baseline", "value", "ms_per_step")},
+        "also": also,
+        "paper_context": PAPER_CONTEXT,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -25,6 +25,7 @@ static void free_device(asp_handle *h) {
     (void)hipFree(h->d_values);
     (void)hipFree(h->d_tasks);
     (void)hipFree(h->d_zero_windows);
+    (void)hipFree(h->d_rank_info);
     if (cur >= 0 && cur != h->device) (void)hipSetDevice(cur);
 }
 
@@ -62,6 +63,9 @@ static asp_status_t create_impl(const asp_config_t *cfg, int64_t m, int64_t k, i
         if ((s = upload(&h->d_row_ptr, h->hb.block_row_ptr.data(), h->hb.block_row_ptr.size() * 4, stream))) return s;
         if ((s = upload(&h->d_col_idx, h->hb.block_col_idx.data(), h->hb.block_col_idx.size() * 4, stream))) return s;
         if ((s = upload(&h->d_values, h->hb.packed.data(), h->hb.packed.size(), stream))) return s;
+        ASP_HIP_TRY(hipDeviceGetAttribute(&h->n_cus, hipDeviceAttributeMultiprocessorCount, h->device));
+        bcsr_build_schedule(h->hb);
+        if ((s = upload(&h->d_rank_info, h->hb.rank_info.data(), h->hb.rank_info.size() * 4, stream))) return s;
         ASP_HIP_TRY(hipStreamSynchronize(stream));
         std::vector<uint8_t>().swap(h->hb.packed);  // the device copy is the only user
         return ASP_OK;

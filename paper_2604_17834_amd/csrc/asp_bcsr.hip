@@ -1,11 +1,15 @@
-// BCSR x dense SpMM for gfx950 (paper, Sections III-A..III-C re-designed for CDNA4; Section IV-C for
-// the tile-width rule).
+// BCSR x dense SpMM for gfx950: dispatch (tile-width rule of the paper's Section IV-C) and the
+// register-staged kernel.
+//
+// The register-staged kernel is the synchronous-copy design (the analogue of the paper's Section III-A
+// kernel with cooperative loads, plus one slice of prefetch): global loads go to VGPRs, then to LDS.  It
+// serves operands that do not allow 16-byte accesses (element-wise path) and stays selectable for
+// comparison runs; aligned operands take the direct-to-LDS ring kernel in asp_bcsr_dma.hip.
 //
 // One workgroup computes one (block-row, N-tile) output tile of b_row x BN: it walks the stored blocks
 // of its block-row (Section II-C), and for each K slice of a block stages the A slice and the matching
 // rows of B through LDS, double buffered, while the previous slice is multiplied on the matrix cores
-// (v_mfma_f32_32x32x16_bf16, fp32 accumulation).  What the paper does with TMA + a producer warpgroup
-// is done here with register-staged global loads issued one slice ahead and two workgroups per CU.
+// (v_mfma_f32_32x32x16_bf16, fp32 accumulation).
 //
 // Operand layouts
 //   A  blocks are pre-permuted on the host into MFMA fragment order, so a slice is one contiguous,
@@ -16,6 +20,9 @@
 //   The MFMA is issued with the operands swapped (B fragment first), so each lane ends with 4
 //   consecutive columns of one output row: the tile is rounded to bf16, passed through LDS and written
 //   to C with 16-byte row-contiguous stores.
+#include <cstdlib>
+#include <cstring>
+
 #include "asp_internal.h"
 
 namespace asp {
@@ -67,7 +74,7 @@ __device__ __forceinline__ uint4 load_b_chunk_scalar(const uint16_t *__restrict_
 }
 
 template <int BR, int BC, int BN, int WM, int WN, bool VEC>
-__global__ __launch_bounds__(WM *WN * 64) void bcsr_spmm_kernel(
+__global__ __launch_bounds__(WM *WN * 64, 2) void bcsr_spmm_kernel(
     const int32_t *__restrict__ block_row_ptr, const int32_t *__restrict__ block_col_idx,
     const uint16_t *__restrict__ a_packed, const uint16_t *__restrict__ B, uint16_t *__restrict__ C, int M, int K,
     int N, int n_brows, int n_tiles, int tiles_per_xcd) {
@@ -270,7 +277,15 @@ asp_status_t bcsr_spmm_launch(const asp_handle *h, const void *B, void *C, int64
     const BcsrPlan p = bcsr_plan(h, N, aligned);
     if (p.workgroups * 8 >= (1ll << 31)) return fail(ASP_ERR_UNSUPPORTED, "too many output tiles");
     const int key = h->b_row * 1000 + p.bn;
-    if (!p.vectorized) {
+    // benchmarking switch only: ASP_BCSR_KERNEL=regstage selects the synchronous-copy kernel
+    static const bool force_regstage = [] {
+        const char *e = std::getenv("ASP_BCSR_KERNEL");
+        return e && std::strcmp(e, "regstage") == 0;
+    }();
+    if (p.vectorized && !force_regstage && N < (1ll << 25)) {
+        if (!bcsr_dma_launch(h, B, C, N, p, stream))
+            return fail(ASP_ERR_UNSUPPORTED, "no kernel for this block size / tile width");
+    } else if (!p.vectorized) {  // element-wise path
         switch (h->b_row) {
             case 128: launch<128, 64, 2, 2, false>(h, B, C, N, p, stream); break;
             case 64: launch<64, 64, 2, 2, false>(h, B, C, N, p, stream); break;

@@ -1,0 +1,499 @@
+// BCSR x dense SpMM, main gfx950 kernel: resident workgroups that stream K slices through an LDS ring
+// filled by direct-to-LDS loads, without ever waiting for their own stores.
+//
+// Decomposition: an output tile is one (block-row, N-tile) pair of b_row x BN; its K loop walks the
+// stored blocks of the block-row (paper, Section II-C) in slices of 32 k; each slice is multiplied with
+// v_mfma_f32_32x32x16_bf16 (fp32 accumulation), operands swapped so that a lane ends with 4 adjacent
+// output columns; the finished tile is rounded to bf16, transposed through LDS and stored as full
+// 128-byte row segments.
+//
+// Asynchronous copy (the role TMA plays in the paper's Section III-B): global->LDS traffic never
+// touches VGPRs.  Each wave issues global_load_lds_dwordx4 instructions, each dropping 64 lanes x 16
+// bytes into one contiguous 1 KB LDS region while the lanes' global source addresses are free.
+// Because the LDS side of such a load is lane-linear, the B slice cannot be padded per row; instead the
+// source chunk of every lane is permuted so that row r's 64-byte units land XOR-swizzled by (r & 3):
+// the four rows touched by one transposing read (ds_read_b64_tr_b16) then fall into disjoint banks.
+// Rows of B past K (zero padding of A's last block column) and 16-byte chunks past N are redirected to
+// the last valid row / chunk: they meet zeros of A or feed columns that are never stored.
+//
+// One continuous pipeline per workgroup.  A workgroup owns a fixed sequence of tiles and treats their
+// slices as one stream: the ring (NS buffers) is refilled one slice per step, and the prefetch cursor
+// runs on into the next tile while the current one is finished, so a tile's first loads overlap the
+// previous tile's last multiplications, its epilogue and its stores.  Per step there is one fence-free
+// barrier and one exact s_waitcnt: the wave counts every vector-memory operation it issues (loads of
+// each slice, stores of each epilogue) and waits only until the operations issued after the slice it
+// needs are the only ones outstanding.  Nothing ever waits for stores to C; with tiles of 1-10 blocks
+// the store drain time of a tile is comparable to its multiply time, so waiting for it (a fenced
+// barrier, or the end of a one-tile workgroup) left the matrix cores idle most of the time.
+// The epilogue stages 32 x 64 pieces of the wave's tile in the one ring buffer that is free at a tile
+// boundary, wave-privately, so it needs a single extra barrier per tile.
+//
+// Scheduling (Sections III-E/III-F of the paper discuss persistent kernels and dynamic tile scheduling
+// on Hopper and reject them there for imbalance and atomic traffic).  Here the assignment is static and
+// balanced by construction: block-rows are sorted by length once per handle; the tile order walks
+// group_n adjacent N-tiles together, heaviest block-rows first; the order is cut into 8 runs of equal
+// weight, one per XCD (workgroup id mod 8 -- workgroups are dealt to XCDs round-robin), so the B column
+// slabs of a group stay in that XCD's private L2 and A blocks are fetched once per group; inside a run
+// the XCD's workgroups take tiles round-robin, which deals sorted weights evenly.
+#include <cstdlib>
+
+#include "asp_internal.h"
+
+namespace asp {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) short short4v;
+typedef __attribute__((ext_vector_type(8))) short short8v;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+
+// s_waitcnt vmcnt(N) lgkmcnt(0): at most N vector-memory operations (the newest ones) stay in flight,
+// every LDS access and scalar load of this wave has completed
+template <int N>
+__device__ __forceinline__ void wait_vmcnt_and_lds() {
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (0 << 8));
+}
+
+// Workgroup barrier without the memory fence of __syncthreads(): the fence would drain vmcnt to zero and
+// with it the slices and stores that are meant to stay in flight.  Callers wait for what they need first.
+__device__ __forceinline__ void barrier_no_fence() { __builtin_amdgcn_s_barrier(); }
+
+// global_load_lds_dwordx4: LDS[lds_base + lane*16 .. +16) = 16 bytes at this lane's source address;
+// lds_base is wave-uniform (it travels in M0).  Issued as inline assembly on purpose: for the builtin
+// form the compiler cannot tell which LDS bytes the copy writes and drains vmcnt to zero before every
+// later LDS read, which would serialise the ring.  Completion is tracked by hand.
+// Form 1: per-lane 64-bit address.  Form 2: wave-uniform 64-bit base + per-lane 32-bit byte offset.
+// The wave-uniform operands are passed through readfirstlane so that they sit in SGPRs even where the
+// compiler's divergence analysis cannot prove that they are uniform.
+__device__ __forceinline__ uint32_t uniform32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+__device__ __forceinline__ const void *uniform_ptr(const void *p) {
+    const uint64_t v = (uint64_t)(uintptr_t)p;
+    const uint64_t lo = uniform32((uint32_t)v), hi = uniform32((uint32_t)(v >> 32));
+    return (const void *)(uintptr_t)(lo | (hi << 32));
+}
+__device__ __forceinline__ void dma16_to_lds(const void *gptr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(uniform32(lds_base))
+                 : "memory", "m0");
+}
+__device__ __forceinline__ void dma16_to_lds(const void *sbase, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(uniform_ptr(sbase)),
+                 "s"(uniform32(lds_base))
+                 : "memory", "m0");
+}
+__device__ __forceinline__ uint32_t lds_offset(const void *p) { return (uint32_t)(uintptr_t)(lds_void_ptr)p; }
+
+// C is written once and not read again by this kernel: keep it from displacing B slabs in L2
+__device__ __forceinline__ void store_c16(uint16_t *dst, uint4 v) {
+    typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+    u32x4 w = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(w, (u32x4 *)dst);
+}
+
+template <int BR, int BN, int WM, int WN, int NS>
+struct DmaCfg {
+    static constexpr int KS = 32;
+    static constexpr int NW = WM * WN;
+    static constexpr int NT = NW * 64;
+    static constexpr int TM = BR / WM, TN = BN / WN;
+    static constexpr int MT = TM / 32, NTL = TN / 32;
+    static constexpr int KK = KS / 16;
+    static constexpr int SPB = BR / KS;             // slices per block (square blocks)
+    static constexpr int A_STAGE = BR * KS * 2;     // bytes
+    static constexpr int B_ROW = BN * 2;            // bytes per LDS row of B
+    static constexpr int B_STAGE = KS * B_ROW;
+    static constexpr int STAGE = A_STAGE + B_STAGE;
+    static constexpr int A_R = A_STAGE / 1024, B_R = B_STAGE / 1024;  // 1 KB regions = wave-level loads
+    static constexpr int A_LPW = A_R / NW, B_LPW = B_R / NW, LPW = A_LPW + B_LPW;
+    static constexpr int CPRW = BN / 8;             // 16-byte chunks per B row
+    // epilogue: a wave stages pieces of 32 rows x RW columns, privately, inside one ring buffer
+    static constexpr int RW = (TN >= 64 && NW * 32 * (64 * 2 + 16) <= STAGE) ? 64 : 32;
+    static constexpr int JR = RW / 32;              // MFMA tiles per piece
+    static constexpr int C_PITCH = RW * 2 + 16;     // bytes
+    static constexpr int C_WAVE = 32 * C_PITCH;
+    static constexpr int CPR = RW / 8;              // 16-byte units per staged row
+    static constexpr int RPI = 64 / CPR;            // rows per wave-level store
+    static constexpr int NSTORE = MT * (TN / RW) * (32 / RPI);  // store instructions per wave and tile
+    static constexpr int LDS_BYTES = NS * STAGE;
+    static_assert(A_R % NW == 0 && B_R % NW == 0, "regions must split evenly over the waves");
+    static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be made of 32x32 MFMA tiles");
+    static_assert(NW * C_WAVE <= STAGE, "epilogue staging must fit into one ring buffer");
+    static_assert(NS == 3, "the wait table below is written for a ring of three");
+    static_assert(NSTORE + 2 * LPW < 64, "vmcnt is a 6-bit counter");
+    // swizzle of a row's 64-byte units: rows k..k+3 of a transposing read must not share banks
+    __device__ static __forceinline__ int swz(int r) { return BN >= 128 ? (r & 3) : ((r >> 1) & 1); }
+};
+
+// first tile of each XCD's run of the tile order, start[8] = number of tiles
+struct XcdRuns {
+    int start[9];
+};
+
+// rank_info[r] = {block-row, first stored block, number of stored blocks, 0} of the r-th heaviest block-row
+template <int BR, int BN, int WM, int WN, int NS>
+__global__ __launch_bounds__(WM *WN * 64, 2) void bcsr_spmm_dma_kernel(
+    const int4 *__restrict__ rank_info, const int32_t *__restrict__ block_col_idx,
+    const uint16_t *__restrict__ a_packed, const uint16_t *__restrict__ B, uint16_t *__restrict__ C, int M, int K,
+    int N, int n_brows, int n_tiles, int group_n, XcdRuns runs) {
+    using Cfg = DmaCfg<BR, BN, WM, WN, NS>;
+    constexpr int NW = Cfg::NW, KS = Cfg::KS, MT = Cfg::MT, NTL = Cfg::NTL, LPW = Cfg::LPW;
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[Cfg::LDS_BYTES];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+
+    // ---- this workgroup's tiles: every stride-th tile of its XCD's run ------------------------------
+    const int xcd = blockIdx.x & 7, stride = gridDim.x >> 3;
+    const int run_end = __builtin_amdgcn_readfirstlane(runs.start[xcd + 1]);
+    int idx_cur = __builtin_amdgcn_readfirstlane(runs.start[xcd]) + (blockIdx.x >> 3);
+    if (idx_cur >= run_end) return;
+
+    // ---- lane-invariant parts of the LDS read addresses ------------------------------------------
+    const int a_off = lane * 16;
+    // transposing read: lane i of a 16-lane group addresses row (i/4), 4 columns at 4*(i%4)
+    const int krow_lane = 8 * (lane >> 5) + ((lane & 15) >> 2);          // + 16*kk (+4 for the upper half)
+    const int sw = Cfg::swz(krow_lane) << 2;                              // same for krow_lane + 4 and + 16
+    const int c_lane = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);         // chunk inside the 32-column tile
+    const int sub = 8 * (lane & 1);                                       // byte inside the chunk
+    int b_off[NTL];
+#pragma unroll
+    for (int j = 0; j < NTL; ++j) {
+        const int c = (wn * Cfg::TN + j * 32) / 8 + c_lane;
+        b_off[j] = krow_lane * Cfg::B_ROW + ((c ^ sw) * 16) + sub;
+    }
+    // B source: region jb = i*NW + wave of a slice holds the 16-byte slots [jb*64, jb*64+64); slot s is
+    // row s / CPRW, position s % CPRW; the position is the swizzled chunk index.
+    int b_row_in_slice[Cfg::B_LPW], b_chunk[Cfg::B_LPW];
+#pragma unroll
+    for (int i = 0; i < Cfg::B_LPW; ++i) {
+        const int s = (i * NW + wave) * 64 + lane;
+        const int r = s / Cfg::CPRW, cp = s % Cfg::CPRW;
+        b_row_in_slice[i] = r;
+        b_chunk[i] = cp ^ (Cfg::swz(r) << 2);
+    }
+    const uint32_t a_voff = (uint32_t)(wave * 1024 + lane * 16);
+    const uint32_t lds0 = lds_offset(lds);
+
+    // ---- tile parameters: two slots, the tile being multiplied and the one after it -------------
+    struct Tile {
+        int br, n0, blk0, T;
+    };
+    // (named objects and selects instead of arrays indexed at run time: such arrays would be placed in
+    // LDS or scratch, and everything read back from there counts as lane-varying for the compiler)
+    Tile tile0, tile1;
+    uint32_t b_voff0[Cfg::B_LPW], b_voff1[Cfg::B_LPW];  // per-lane byte offsets of the B loads within a slice
+    auto tile_T = [&](int slot) { return slot ? tile1.T : tile0.T; };
+    auto decode = [&](int idx, Tile &t, uint32_t (&voff)[Cfg::B_LPW]) {
+        const int per_group = group_n * n_brows;
+        const int grp = idx / per_group, in_grp = idx - grp * per_group;
+        const int left = n_tiles - grp * group_n;
+        const int gw = left < group_n ? left : group_n;  // the last group may be narrower
+        const int rank = in_grp / gw, nt = grp * group_n + (in_grp - rank * gw);
+        const int4 ri = rank_info[rank];
+        // the index is the same for the whole workgroup: tell the compiler, so that everything derived
+        // from a tile's parameters stays in scalar registers
+        t.br = __builtin_amdgcn_readfirstlane(ri.x);
+        t.blk0 = __builtin_amdgcn_readfirstlane(ri.y);
+        t.T = __builtin_amdgcn_readfirstlane(ri.z) * Cfg::SPB;
+        t.n0 = nt * BN;
+#pragma unroll
+        for (int i = 0; i < Cfg::B_LPW; ++i) {
+            int col = t.n0 + 8 * b_chunk[i];
+            col = col < N ? col : N - 8;  // chunks past N only feed columns that are never stored
+            voff[i] = (uint32_t)(((int64_t)b_row_in_slice[i] * N + col) * 2);
+        }
+    };
+
+    // ---- the slice stream ---------------------------------------------------------------------------
+    // cur: slot of the tile being multiplied.  The prefetch cursor (pf_slot, pf_t) is the next slice to
+    // request; it is in the current tile (pf_ahead = 0) or in the next one (pf_ahead = 1), never further.
+    // Buffers buf_c, buf_c+1, .. (mod NS) hold the `inflight` slices requested but not yet multiplied.
+    // issued counts the vector-memory operations of this wave; mark[b] is its value right after the
+    // loads into buffer b were issued, so issued - mark[b] operations may remain outstanding when the
+    // content of b is needed (the counter retires in order).
+    int cur = 0, have_next = 0;
+    int pf_slot = 0, pf_t = 0, pf_ahead = 0;
+    int buf_c = 0, inflight = 0;
+    int issued = 0, mark0 = 0, mark1 = 0, mark2 = 0;
+    auto mark_of = [&](int b) { return b == 0 ? mark0 : (b == 1 ? mark1 : mark2); };
+
+    decode(idx_cur, tile0, b_voff0);
+    tile1 = tile0;
+#pragma unroll
+    for (int i = 0; i < Cfg::B_LPW; ++i) b_voff1[i] = b_voff0[i];
+    if (idx_cur + stride < run_end) {
+        have_next = 1;
+        decode(idx_cur + stride, tile1, b_voff1);
+    }
+
+    auto issue_slice = [&](const Tile &tl, const uint32_t (&voff)[Cfg::B_LPW], int t, int buf) {
+        const int p = tl.blk0 + t / Cfg::SPB, s = t % Cfg::SPB;
+        const uint32_t stage = lds0 + buf * Cfg::STAGE;
+        const uint8_t *abase = (const uint8_t *)(a_packed + (int64_t)p * (BR * BR) + (int64_t)s * (BR * KS));
+#pragma unroll
+        for (int i = 0; i < Cfg::A_LPW; ++i)
+            dma16_to_lds(abase + i * NW * 1024, a_voff, stage + (i * NW + wave) * 1024);
+        const int krow0 = __builtin_amdgcn_readfirstlane(block_col_idx[p]) * BR + s * KS;
+        const uint8_t *bbase = (const uint8_t *)(B + (int64_t)krow0 * N);
+        if (krow0 + KS <= K) {
+#pragma unroll
+            for (int i = 0; i < Cfg::B_LPW; ++i)
+                dma16_to_lds(bbase, voff[i], stage + Cfg::A_STAGE + (i * NW + wave) * 1024);
+        } else {
+            // the slice crosses K: rows past K are read from row K-1, they meet the zero padding of A
+#pragma unroll
+            for (int i = 0; i < Cfg::B_LPW; ++i) {
+                int krow = krow0 + b_row_in_slice[i];
+                int back = krow < K ? 0 : krow - (K - 1);
+                dma16_to_lds(bbase + voff[i] - (int64_t)back * N * 2, stage + Cfg::A_STAGE + (i * NW + wave) * 1024);
+            }
+        }
+    };
+    // request the next slice of the stream, if there is one within reach; returns whether it did
+    auto prefetch_one = [&]() -> bool {
+        if (pf_t >= tile_T(pf_slot)) {  // this tile is fully requested: step into the next one
+            if (pf_ahead != 0 || !have_next) return false;
+            pf_slot ^= 1;
+            pf_ahead = 1;
+            pf_t = 0;
+            if (tile_T(pf_slot) == 0) return false;
+        }
+        int buf = buf_c + inflight;
+        buf = buf >= NS ? buf - NS : buf;
+        if (pf_slot == 0) issue_slice(tile0, b_voff0, pf_t, buf);
+        else issue_slice(tile1, b_voff1, pf_t, buf);
+        issued += LPW;
+        mark0 = buf == 0 ? issued : mark0;
+        mark1 = buf == 1 ? issued : mark1;
+        mark2 = buf == 2 ? issued : mark2;
+        ++pf_t;
+        ++inflight;
+        return true;
+    };
+    // wait until at most `allowed` of this wave's vector-memory operations are outstanding (rounded
+    // down to one of the counts that can occur), and until its LDS accesses and scalar loads are done
+    auto wait_outstanding = [&](int allowed) {
+        constexpr int S = Cfg::NSTORE;
+        if (allowed >= S + 2 * LPW) wait_vmcnt_and_lds<S + 2 * LPW>();
+        else if (allowed >= S + LPW) wait_vmcnt_and_lds<S + LPW>();
+        else if (allowed >= S && S > 2 * LPW) wait_vmcnt_and_lds<S>();
+        else if (allowed >= 2 * LPW) wait_vmcnt_and_lds<2 * LPW>();
+        else if (allowed >= S) wait_vmcnt_and_lds<S>();
+        else if (allowed >= LPW) wait_vmcnt_and_lds<LPW>();
+        else wait_vmcnt_and_lds<0>();
+    };
+
+    auto compute_slice = [&](f32x16 (&acc)[MT][NTL], int buf) {
+        const uint8_t *sa = lds + buf * Cfg::STAGE, *sb = sa + Cfg::A_STAGE;
+#pragma unroll
+        for (int kk = 0; kk < Cfg::KK; ++kk) {
+            bf16x8 af[MT], bfr[NTL];
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+                af[i] = *(const bf16x8 *)(sa + (kk * (BR / 32) + wm * MT + i) * 1024 + a_off);
+#pragma unroll
+            for (int j = 0; j < NTL; ++j) {
+                const uint8_t *p0 = sb + kk * 16 * Cfg::B_ROW + b_off[j];
+                short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3))) *)(p0));
+                short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (short4v __attribute__((address_space(3))) *)(p0 + 4 * Cfg::B_ROW));
+                short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                bfr[j] = __builtin_bit_cast(bf16x8, both);
+            }
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NTL; ++j)
+                    // operands swapped: D[n][m] = sum_k B[k][n] * A[m][k]
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    for (;;) {
+        const Tile tc = cur ? tile1 : tile0;
+        // (re)fill the ring up to NS-1 slices: the buffer behind buf_c may still be read as the previous
+        // tile's staging area until the next barrier
+        while (inflight < NS - 1 && prefetch_one()) {
+        }
+        f32x16 acc[MT][NTL];
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NTL; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+        for (int t = 0; t < tc.T; ++t) {
+            wait_outstanding(issued - mark_of(buf_c));  // this wave's part of the slice in buf_c has landed
+            barrier_no_fence();                      // everybody's part has; the buffer behind buf_c is free
+            while (inflight < NS && prefetch_one()) {
+            }
+            compute_slice(acc, buf_c);
+            buf_c = buf_c + 1 == NS ? 0 : buf_c + 1;
+            --inflight;
+        }
+
+        // ---- tile boundary ------------------------------------------------------------------------
+        // parameters of the tile after the next one: requested now, needed after the epilogue
+        const int idx_nn = idx_cur + 2 * stride;
+        Tile tnn = tc;
+        uint32_t voff_nn[Cfg::B_LPW];
+#pragma unroll
+        for (int i = 0; i < Cfg::B_LPW; ++i) voff_nn[i] = 0;
+        if (idx_nn < run_end) decode(idx_nn, tnn, voff_nn);
+
+        // the buffer behind buf_c holds nothing that is still needed once every wave got here
+        wait_vmcnt_and_lds<63>();
+        barrier_no_fence();
+        int sbuf = buf_c == 0 ? NS - 1 : buf_c - 1;
+        uint8_t *sc = lds + sbuf * Cfg::STAGE + wave * Cfg::C_WAVE;
+        const bool interior = tc.br * BR + BR <= M && tc.n0 + BN <= N;
+        const int grow0 = tc.br * BR + wm * Cfg::TM + lane / Cfg::CPR;
+        const int gcol0 = tc.n0 + wn * Cfg::TN + (lane % Cfg::CPR) * 8;
+        const uint8_t *scl = sc + (lane / Cfg::CPR) * Cfg::C_PITCH + (lane % Cfg::CPR) * 16;
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int jh = 0; jh < NTL / Cfg::JR; ++jh) {
+                // fp32 -> bf16 (round to nearest even); lane holds row (lane & 31), 4 adjacent columns per q
+#pragma unroll
+                for (int jj = 0; jj < Cfg::JR; ++jj)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const f32x16 &a = acc[i][jh * Cfg::JR + jj];
+                        f32x4 v = {a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]};
+                        bf16x4 hv = __builtin_convertvector(v, bf16x4);
+                        *(bf16x4 *)(sc + (lane & 31) * Cfg::C_PITCH + (jj * 32 + 8 * q + 4 * (lane >> 5)) * 2) = hv;
+                    }
+                // LDS is in order within a wave: the reads below see the writes above
+                uint16_t *cdst = C + (int64_t)(grow0 + i * 32) * N + gcol0 + jh * Cfg::RW;
+                if (interior) {
+#pragma unroll
+                    for (int it = 0; it < 32 / Cfg::RPI; ++it) {
+                        uint4 v = *(const uint4 *)(scl + it * Cfg::RPI * Cfg::C_PITCH);
+                        store_c16(cdst + (int64_t)it * Cfg::RPI * N, v);
+                    }
+                } else {
+#pragma unroll
+                    for (int it = 0; it < 32 / Cfg::RPI; ++it) {
+                        uint4 v = *(const uint4 *)(scl + it * Cfg::RPI * Cfg::C_PITCH);
+                        if (grow0 + i * 32 + it * Cfg::RPI < M && gcol0 + jh * Cfg::RW < N)
+                            store_c16(cdst + (int64_t)it * Cfg::RPI * N, v);
+                    }
+                }
+            }
+        if (interior) {
+            issued += Cfg::NSTORE;  // exactly NSTORE stores were issued, none is waited for
+        } else {
+            // an edge tile issues a data-dependent number of stores: drain once so the count is exact again
+            wait_vmcnt_and_lds<0>();
+            mark0 = mark1 = mark2 = issued;
+        }
+
+        // ---- advance to the next tile ---------------------------------------------------------------
+        if (!have_next) break;
+        idx_cur += stride;
+        if (idx_nn < run_end) {
+            if (cur) tile1 = tnn; else tile0 = tnn;
+#pragma unroll
+            for (int i = 0; i < Cfg::B_LPW; ++i) {
+                if (cur) b_voff1[i] = voff_nn[i]; else b_voff0[i] = voff_nn[i];
+            }
+            have_next = 1;
+        } else {
+            have_next = 0;
+        }
+        cur ^= 1;
+        if (pf_ahead) {
+            pf_ahead = 0;  // the cursor's tile is now the current one
+        } else {           // the cursor never left the finished tile (its successor was empty or absent)
+            pf_slot = cur;
+            pf_t = 0;
+        }
+    }
+}
+
+// ---- host side ------------------------------------------------------------------------------------
+
+// Cut the tile order into 8 runs of equal weight.  Tile weight = stored blocks of its block-row + 1
+// (the 1 stands for the epilogue).  Groups of N-tiles repeat the same sorted list of block-rows, so a
+// cut is found from the per-handle prefix sums over that list.
+static XcdRuns cut_runs(const asp_handle *h, int n_tiles, int group_n) {
+    const std::vector<int64_t> &pre = h->hb.sorted_weight_prefix;  // [n_brows + 1]
+    const int64_t nbr = h->n_brows;
+    const int64_t rows_weight = pre[nbr];
+    const int64_t n_groups = ceil_div(n_tiles, group_n);
+    const int64_t total_weight = rows_weight * n_tiles;
+    XcdRuns r;
+    r.start[0] = 0;
+    for (int x = 1; x < 8; ++x) {
+        const int64_t target = total_weight * x / 8;
+        // whole groups before the cut
+        int64_t g = 0, acc = 0;
+        for (; g < n_groups; ++g) {
+            const int64_t gw = std::min<int64_t>(group_n, n_tiles - g * group_n);
+            if (acc + gw * rows_weight > target) break;
+            acc += gw * rows_weight;
+        }
+        if (g >= n_groups) {
+            r.start[x] = (int)(nbr * n_tiles);
+            continue;
+        }
+        const int64_t gw = std::min<int64_t>(group_n, n_tiles - g * group_n);
+        // first rank whose prefix (times the group width) reaches the remainder
+        const int64_t rem = target - acc;
+        int64_t lo = 0, hi = nbr;
+        while (lo < hi) {
+            int64_t mid = (lo + hi) / 2;
+            if (pre[mid] * gw < rem) lo = mid + 1; else hi = mid;
+        }
+        r.start[x] = (int)(g * group_n * nbr + lo * gw);
+    }
+    r.start[8] = (int)(nbr * n_tiles);
+    for (int x = 1; x <= 8; ++x)
+        if (r.start[x] < r.start[x - 1]) r.start[x] = r.start[x - 1];
+    return r;
+}
+
+template <int BR, int BN, int WM, int WN, int NS>
+static void launch_dma(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream) {
+    // benchmarking switches only
+    static const int env_group = [] {
+        const char *e = std::getenv("ASP_BCSR_GROUP_N");
+        return e ? std::atoi(e) : 0;
+    }();
+    static const int env_wgs = [] {
+        const char *e = std::getenv("ASP_BCSR_WGS_PER_CU");
+        return e ? std::atoi(e) : 0;
+    }();
+    int group_n = env_group > 0 ? env_group : 4;
+    if (group_n > p.n_tiles) group_n = p.n_tiles;
+    int64_t workers = (int64_t)h->n_cus * (env_wgs > 0 ? env_wgs : 2);
+    if (workers > p.workgroups) workers = p.workgroups;
+    workers = std::max<int64_t>(8, workers / 8 * 8);  // the same number of workgroups on every XCD
+    const XcdRuns runs = cut_runs(h, p.n_tiles, group_n);
+    dim3 grid((unsigned)workers), block(WM * WN * 64);
+    hipLaunchKernelGGL((bcsr_spmm_dma_kernel<BR, BN, WM, WN, NS>), grid, block, 0, stream, (const int4 *)h->d_rank_info,
+                       h->d_col_idx, (const uint16_t *)h->d_values, (const uint16_t *)B, (uint16_t *)C, (int)h->m,
+                       (int)h->k, (int)N, (int)h->n_brows, p.n_tiles, group_n, runs);
+}
+
+// needs N % 8 == 0, 8 <= N < 2^25 and 16-byte aligned B and C (the caller checked)
+bool bcsr_dma_launch(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream) {
+    switch (h->b_row * 1000 + p.bn) {
+        case 128256: launch_dma<128, 256, 2, 2, 3>(h, B, C, N, p, stream); return true;
+        case 128128: launch_dma<128, 128, 2, 2, 3>(h, B, C, N, p, stream); return true;
+        case 128064: launch_dma<128, 64, 2, 2, 3>(h, B, C, N, p, stream); return true;
+        case 64256: launch_dma<64, 256, 1, 4, 3>(h, B, C, N, p, stream); return true;
+        case 64128: launch_dma<64, 128, 2, 2, 3>(h, B, C, N, p, stream); return true;
+        case 64064: launch_dma<64, 64, 1, 2, 3>(h, B, C, N, p, stream); return true;
+        case 32256: launch_dma<32, 256, 1, 2, 3>(h, B, C, N, p, stream); return true;
+        case 32128: launch_dma<32, 128, 1, 2, 3>(h, B, C, N, p, stream); return true;
+        case 32064: launch_dma<32, 64, 1, 2, 3>(h, B, C, N, p, stream); return true;
+    }
+    return false;
+}
+
+}  // namespace asp

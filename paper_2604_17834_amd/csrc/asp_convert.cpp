@@ -133,6 +133,26 @@ void csr_to_bcsr(int64_t m, int64_t k, const int32_t *row_ptr, const int32_t *co
     });
 }
 
+// Scheduling data of the main BCSR kernel: block-rows ordered by their number of stored blocks,
+// heaviest first (ties: lower block-row first), with prefix sums of the tile weights in that order.
+void bcsr_build_schedule(HostBcsr &b) {
+    const int64_t nbr = (int64_t)b.block_row_ptr.size() - 1;
+    std::vector<int32_t> order(nbr);
+    for (int64_t i = 0; i < nbr; ++i) order[i] = (int32_t)i;
+    auto len = [&](int32_t r) { return b.block_row_ptr[r + 1] - b.block_row_ptr[r]; };
+    std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return len(x) > len(y); });
+    b.rank_info.resize((size_t)nbr * 4);
+    b.sorted_weight_prefix.assign(nbr + 1, 0);
+    for (int64_t r = 0; r < nbr; ++r) {
+        const int32_t br = order[r];
+        b.rank_info[4 * r + 0] = br;
+        b.rank_info[4 * r + 1] = b.block_row_ptr[br];
+        b.rank_info[4 * r + 2] = len(br);
+        b.rank_info[4 * r + 3] = 0;
+        b.sorted_weight_prefix[r + 1] = b.sorted_weight_prefix[r] + len(br) + 1;
+    }
+}
+
 // Kernel-internal order of a bf16 block: for each 16-wide k slice, for each group of 32 rows, the 64
 // lanes of a wavefront hold 8 consecutive k each (lane l: row l % 32, k offset 8 * (l / 32)), which
 // is the A/B operand layout of v_mfma_f32_32x32x16_bf16.  A pure permutation of the canonical block.

@@ -32,6 +32,10 @@ struct HostBcsr {
     std::vector<int32_t> block_col_idx;  // [nnz_blocks]
     std::vector<uint8_t> blocks;         // canonical [nnz_blocks][b_row][b_col], raw bytes
     std::vector<uint8_t> packed;         // same values in MFMA-fragment order (kernel-internal)
+    // scheduling data of the main kernel: block-rows sorted by stored blocks (descending) and the
+    // prefix sums of their tile weights (stored blocks + 1) in that order
+    std::vector<int32_t> rank_info;            // [n_brows][4]
+    std::vector<int64_t> sorted_weight_prefix; // [n_brows + 1]
 };
 
 struct HostWcsr {
@@ -45,6 +49,7 @@ struct HostWcsr {
 // converters (asp_convert.cpp); values are only bit-copied
 void csr_to_bcsr(int64_t m, int64_t k, const int32_t *row_ptr, const int32_t *col_idx, const void *values,
                  size_t esize, int32_t b_row, int32_t b_col, HostBcsr &out);
+void bcsr_build_schedule(HostBcsr &b);
 void bcsr_pack_fragments_bf16(const HostBcsr &in, int32_t b_row, int32_t b_col, std::vector<uint8_t> &packed);
 void csr_to_wcsr(int64_t m, int64_t k, const int32_t *row_ptr, const int32_t *col_idx, const void *values,
                  size_t esize, int32_t b_row, int32_t b_col, HostWcsr &out);
@@ -73,6 +78,8 @@ struct asp_handle {
     void *d_values = nullptr;       // BCSR: fragment-packed blocks; WCSR: canonical tiles
     int32_t *d_tasks = nullptr;     // WCSR tasks [n_tasks][4]
     int32_t *d_zero_windows = nullptr;
+    int32_t *d_rank_info = nullptr; // BCSR: [n_brows][4] = {block-row, first block, stored blocks, 0}, heaviest first
+    int n_cus = 0;                  // compute units of the owning device
 };
 
 namespace asp {
@@ -84,6 +91,7 @@ struct BcsrPlan {
     int64_t workgroups;
 };
 BcsrPlan bcsr_plan(const asp_handle *h, int64_t N, bool aligned);
+bool bcsr_dma_launch(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream);
 asp_status_t bcsr_spmm_launch(const asp_handle *h, const void *B, void *C, int64_t N, hipStream_t stream);
 
 struct WcsrPlan {
