@@ -154,6 +154,9 @@ def main():
     ap.add_argument("--workload", default="bcsr_gate_proj")
     ap.add_argument("--also", default="wcsr_zipf", help="comma list of further workloads reported under 'also' ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-reference", action="store_true",
+                    help="only run a plain 1 GiB device copy (3 launches): the kernel of known size against "
+                         "which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (one MI355X, no collectives); run with --gpus 1",
@@ -168,6 +171,15 @@ def main():
         print("bench.py: no GPU visible; the SpMM path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     torch.cuda.set_device(0)
+    if args.copy_reference:
+        x = torch.ones(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB read + 1 GiB written per launch
+        y = torch.empty_like(x)
+        for _ in range(3):
+            y.copy_(x)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_reference_bytes_read": x.numel() * 4, "copy_reference_bytes_written": x.numel() * 4,
+                          "launches": 3}))
+        return
     asp.lib()  # raises when the HIP library has not been built
 
     main_res = run_workload(args.workload, args.steps, args.warmup, torch, asp, synth, not args.no_cpu_baseline)

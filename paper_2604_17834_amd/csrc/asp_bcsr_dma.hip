@@ -84,12 +84,30 @@ __device__ __forceinline__ void dma16_to_lds(const void *sbase, uint32_t voff, u
 }
 __device__ __forceinline__ uint32_t lds_offset(const void *p) { return (uint32_t)(uintptr_t)(lds_void_ptr)p; }
 
-// C is written once and not read again by this kernel: keep it from displacing B slabs in L2
+// 16-byte store of finished output, marked non-temporal: C is written once and never read here, and
+// plain stores were measured ~10 % slower end to end because the written lines displace B slabs in L2
+// (a store-only kernel with this access pattern is faster with plain stores; the product is not).
 __device__ __forceinline__ void store_c16(uint16_t *dst, uint4 v) {
     typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
     u32x4 w = {v.x, v.y, v.z, v.w};
     __builtin_nontemporal_store(w, (u32x4 *)dst);
 }
+
+#ifdef ASP_TRACE
+// Debug builds only: cycle stamps of one wave (workgroup ASP_TRACE_WG, thread 0) are collected in LDS
+// (so that stamping does not touch the vector-memory counter) and copied out when the workgroup ends;
+// asp_debug_read_trace() reads them back.  Event = (tag << 56) | cycle counter.
+#define ASP_TRACE_CAP 480
+__device__ unsigned long long g_trace[ASP_TRACE_CAP];
+__device__ unsigned int g_trace_n;
+#define ASP_STAMP(tag)                                                                             \
+    do {                                                                                           \
+        if (blockIdx.x == ASP_TRACE_WG && threadIdx.x == 0 && trace_n < ASP_TRACE_CAP)             \
+            s_trace[trace_n++] = ((unsigned long long)(tag) << 56) | (__builtin_readcyclecounter() & 0xffffffffffffffull); \
+    } while (0)
+#else
+#define ASP_STAMP(tag) do {} while (0)
+#endif
 
 template <int BR, int BN, int WM, int WN, int NS>
 struct DmaCfg {
@@ -139,6 +157,10 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void bcsr_spmm_dma_kernel(
     using Cfg = DmaCfg<BR, BN, WM, WN, NS>;
     constexpr int NW = Cfg::NW, KS = Cfg::KS, MT = Cfg::MT, NTL = Cfg::NTL, LPW = Cfg::LPW;
     __shared__ __attribute__((aligned(1024))) uint8_t lds[Cfg::LDS_BYTES];
+#ifdef ASP_TRACE
+    __shared__ unsigned long long s_trace[ASP_TRACE_CAP];
+    unsigned int trace_n = 0;
+#endif
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -179,6 +201,7 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void bcsr_spmm_dma_kernel(
     // ---- tile parameters: two slots, the tile being multiplied and the one after it -------------
     struct Tile {
         int br, n0, blk0, T;
+        int bcol0;  // block column of the tile's first stored block (loaded early, see issue_slice)
     };
     // (named objects and selects instead of arrays indexed at run time: such arrays would be placed in
     // LDS or scratch, and everything read back from there counts as lane-varying for the compiler)
@@ -197,6 +220,7 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void bcsr_spmm_dma_kernel(
         t.br = __builtin_amdgcn_readfirstlane(ri.x);
         t.blk0 = __builtin_amdgcn_readfirstlane(ri.y);
         t.T = __builtin_amdgcn_readfirstlane(ri.z) * Cfg::SPB;
+        t.bcol0 = t.T > 0 ? __builtin_amdgcn_readfirstlane(block_col_idx[t.blk0]) : 0;
         t.n0 = nt * BN;
 #pragma unroll
         for (int i = 0; i < Cfg::B_LPW; ++i) {
@@ -215,6 +239,9 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void bcsr_spmm_dma_kernel(
     // content of b is needed (the counter retires in order).
     int cur = 0, have_next = 0;
     int pf_slot = 0, pf_t = 0, pf_ahead = 0;
+    // block column of the block the cursor is in, and of the block after it: an index is always loaded
+    // one block before it is needed, so that no step waits for a dependent scalar load
+    int pf_bcol = 0, pf_bcol_next = 0;
     int buf_c = 0, inflight = 0;
     int issued = 0, mark0 = 0, mark1 = 0, mark2 = 0;
     auto mark_of = [&](int b) { return b == 0 ? mark0 : (b == 1 ? mark1 : mark2); };
@@ -235,7 +262,11 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void bcsr_spmm_dma_kernel(
 #pragma unroll
         for (int i = 0; i < Cfg::A_LPW; ++i)
             dma16_to_lds(abase + i * NW * 1024, a_voff, stage + (i * NW + wave) * 1024);
-        const int krow0 = __builtin_amdgcn_readfirstlane(block_col_idx[p]) * BR + s * KS;
+        if (s == 0) {
+            pf_bcol = t == 0 ? tl.bcol0 : pf_bcol_next;
+            if (t + Cfg::SPB < tl.T) pf_bcol_next = __builtin_amdgcn_readfirstlane(block_col_idx[p + 1]);
+        }
+        const int krow0 = pf_bcol * BR + s * KS;
         const uint8_t *bbase = (const uint8_t *)(B + (int64_t)krow0 * N);
         if (krow0 + KS <= K) {
 #pragma unroll
@@ -325,12 +356,18 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void bcsr_spmm_dma_kernel(
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+        ASP_STAMP(1);
         for (int t = 0; t < tc.T; ++t) {
+            ASP_STAMP(2);
             wait_outstanding(issued - mark_of(buf_c));  // this wave's part of the slice in buf_c has landed
+            ASP_STAMP(3);
             barrier_no_fence();                      // everybody's part has; the buffer behind buf_c is free
+            ASP_STAMP(4);
             while (inflight < NS && prefetch_one()) {
             }
+            ASP_STAMP(5);
             compute_slice(acc, buf_c);
+            ASP_STAMP(6);
             buf_c = buf_c + 1 == NS ? 0 : buf_c + 1;
             --inflight;
         }
@@ -345,8 +382,10 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void bcsr_spmm_dma_kernel(
         if (idx_nn < run_end) decode(idx_nn, tnn, voff_nn);
 
         // the buffer behind buf_c holds nothing that is still needed once every wave got here
+        ASP_STAMP(7);
         wait_vmcnt_and_lds<63>();
         barrier_no_fence();
+        ASP_STAMP(8);
         int sbuf = buf_c == 0 ? NS - 1 : buf_c - 1;
         uint8_t *sc = lds + sbuf * Cfg::STAGE + wave * Cfg::C_WAVE;
         const bool interior = tc.br * BR + BR <= M && tc.n0 + BN <= N;
@@ -392,7 +431,14 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void bcsr_spmm_dma_kernel(
             mark0 = mark1 = mark2 = issued;
         }
 
+        ASP_STAMP(9);
         // ---- advance to the next tile ---------------------------------------------------------------
+#ifdef ASP_TRACE
+        if (!have_next && blockIdx.x == ASP_TRACE_WG && threadIdx.x == 0) {
+            for (unsigned int i = 0; i < trace_n; ++i) g_trace[i] = s_trace[i];
+            g_trace_n = trace_n;
+        }
+#endif
         if (!have_next) break;
         idx_cur += stride;
         if (idx_nn < run_end) {
@@ -495,5 +541,18 @@ bool bcsr_dma_launch(const asp_handle *h, const void *B, void *C, int64_t N, con
     }
     return false;
 }
+
+#ifdef ASP_TRACE
+extern "C" int asp_debug_read_trace(unsigned long long *dst, unsigned int cap) {
+    unsigned int n = 0;
+    if (hipMemcpyFromSymbol(&n, HIP_SYMBOL(g_trace_n), sizeof(n)) != hipSuccess) return -1;
+    if (n > cap) n = cap;
+    if (n > ASP_TRACE_CAP) n = ASP_TRACE_CAP;
+    if (hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_trace), (size_t)n * 8) != hipSuccess) return -1;
+    unsigned int zero = 0;
+    (void)hipMemcpyToSymbol(HIP_SYMBOL(g_trace_n), &zero, sizeof(zero));
+    return (int)n;
+}
+#endif
 
 }  // namespace asp
