@@ -255,8 +255,16 @@ static int choose_bn(int64_t N, const int *cand, int n) {
 BcsrPlan bcsr_plan(const asp_handle *h, int64_t N, bool aligned) {
     BcsrPlan p;
     p.vectorized = (aligned && N % 8 == 0) ? 1 : 0;
-    static const int cand[3] = {64, 128, 256};
-    p.bn = p.vectorized ? choose_bn(N, cand, 3) : 64;  // the element-wise path is only built for BN = 64
+    static const int cand[4] = {64, 128, 256, 512};
+    // 512-wide tiles are only built for 128x128 blocks and only pay when there are enough tiles per CU
+    const int ncand = (h->b_row == 128 && std::getenv("ASP_BCSR_BN512")) ? 4 : 3;
+    p.bn = p.vectorized ? choose_bn(N, cand, ncand) : 64;  // the element-wise path is only built for BN = 64
+    // benchmarking switch only: ASP_BCSR_BN forces a narrower tile (it must be one of the built widths)
+    static const int env_bn = [] {
+        const char *e = std::getenv("ASP_BCSR_BN");
+        return e ? std::atoi(e) : 0;
+    }();
+    if (p.vectorized && (env_bn == 64 || env_bn == 128 || env_bn == 256) && env_bn < p.bn) p.bn = env_bn;
     p.n_tiles = (int32_t)ceil_div(N, p.bn);
     p.workgroups = h->n_brows * p.n_tiles;
     return p;

@@ -78,6 +78,9 @@ __device__ __forceinline__ void dma16_to_lds(const void *gptr, uint32_t lds_base
                  : "memory", "m0");
 }
 __device__ __forceinline__ void dma16_to_lds(const void *sbase, uint32_t voff, uint32_t lds_base) {
+#ifdef ASP_DBG_NOLOAD
+    return;
+#endif
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(uniform_ptr(sbase)),
                  "s"(uniform32(lds_base))
                  : "memory", "m0");
@@ -88,6 +91,9 @@ __device__ __forceinline__ uint32_t lds_offset(const void *p) { return (uint32_t
 // plain stores were measured ~10 % slower end to end because the written lines displace B slabs in L2
 // (a store-only kernel with this access pattern is faster with plain stores; the product is not).
 __device__ __forceinline__ void store_c16(uint16_t *dst, uint4 v) {
+#ifdef ASP_DBG_NOSTORE
+    if (v.x != 0x12345678u) return;
+#endif
     typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
     u32x4 w = {v.x, v.y, v.z, v.w};
     __builtin_nontemporal_store(w, (u32x4 *)dst);
@@ -516,7 +522,10 @@ static void launch_dma(const asp_handle *h, const void *B, void *C, int64_t N, c
     }();
     int group_n = env_group > 0 ? env_group : 4;
     if (group_n > p.n_tiles) group_n = p.n_tiles;
-    int64_t workers = (int64_t)h->n_cus * (env_wgs > 0 ? env_wgs : 2);
+    // resident workgroups per CU: as many as LDS allows (the kernel is built for 2 waves per SIMD)
+    const int fit = (int)(163840 / DmaCfg<BR, BN, WM, WN, NS>::LDS_BYTES);
+    const int per_cu = std::max(1, std::min(fit, 8 / (WM * WN)));
+    int64_t workers = (int64_t)h->n_cus * (env_wgs > 0 ? env_wgs : per_cu);
     if (workers > p.workgroups) workers = p.workgroups;
     workers = std::max<int64_t>(8, workers / 8 * 8);  // the same number of workgroups on every XCD
     const XcdRuns runs = cut_runs(h, p.n_tiles, group_n);
@@ -529,6 +538,7 @@ static void launch_dma(const asp_handle *h, const void *B, void *C, int64_t N, c
 // needs N % 8 == 0, 8 <= N < 2^25 and 16-byte aligned B and C (the caller checked)
 bool bcsr_dma_launch(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream) {
     switch (h->b_row * 1000 + p.bn) {
+        case 128512: launch_dma<128, 512, 2, 4, 3>(h, B, C, N, p, stream); return true;
         case 128256: launch_dma<128, 256, 2, 2, 3>(h, B, C, N, p, stream); return true;
         case 128128: launch_dma<128, 128, 2, 2, 3>(h, B, C, N, p, stream); return true;
         case 128064: launch_dma<128, 64, 2, 2, 3>(h, B, C, N, p, stream); return true;

@@ -13,6 +13,8 @@
 //
 // The paper fixes the window height at 64 to fit the Hopper instruction; the CDNA fp32 MFMAs are
 // 16 or 32 rows tall, so heights 16 (default), 32 and 64 are built.
+#include <cstdlib>
+
 #include "asp_internal.h"
 
 namespace asp {
@@ -95,38 +97,61 @@ __global__ __launch_bounds__(256) void wcsr16_spmm_kernel(const int4 *__restrict
 #pragma unroll
         for (int t = 0; t < 4; ++t) acc[g][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    struct Stage {
-        float a[2];
-        float4 b[2][NG];
+    // Software pipeline over chunks of D tiles (D*8 packed columns): while chunk c is multiplied, the B
+    // rows and A values of chunk c+1 are in flight and the column indices of chunk c+2 are being read,
+    // so neither the index -> address dependency nor the gather latency is waited for in the loop.
+    constexpr int D = NG >= 2 ? 1 : 2;
+    struct Chunk {
+        float a[D][2];
+        float4 b[D][2][NG];
     };
-    auto fetch = [&](int tile, Stage &s) {
+    const int tile0 = td.y >> 3, tile1 = td.z >> 3;
+    auto load_idx = [&](int base, int (&idx)[D][2]) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int col = window_col_idx[tile * 8 + 4 * h + kq];
-            s.a[h] = values[(int64_t)tile * 128 + jl * 8 + 4 * h + kq];
+        for (int d = 0; d < D; ++d)
 #pragma unroll
-            for (int g = 0; g < NG; ++g) s.b[h][g] = gather4(B, col, N, n0 + 64 * g, VEC);
-        }
+            for (int h = 0; h < 2; ++h)
+                idx[d][h] = base + d < tile1 ? window_col_idx[(base + d) * 8 + 4 * h + kq] : -1;
     };
-    auto multiply = [&](const Stage &s) {
+    auto gather = [&](int base, const int (&idx)[D][2], Chunk &c) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
+        for (int d = 0; d < D; ++d)
 #pragma unroll
-            for (int g = 0; g < NG; ++g) {
-                acc[g][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(s.a[h], s.b[h][g].x, acc[g][0], 0, 0, 0);
-                acc[g][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(s.a[h], s.b[h][g].y, acc[g][1], 0, 0, 0);
-                acc[g][2] = __builtin_amdgcn_mfma_f32_16x16x4f32(s.a[h], s.b[h][g].z, acc[g][2], 0, 0, 0);
-                acc[g][3] = __builtin_amdgcn_mfma_f32_16x16x4f32(s.a[h], s.b[h][g].w, acc[g][3], 0, 0, 0);
+            for (int h = 0; h < 2; ++h) {
+                c.a[d][h] = base + d < tile1 ? values[(int64_t)(base + d) * 128 + jl * 8 + 4 * h + kq] : 0.f;
+#pragma unroll
+                for (int g = 0; g < NG; ++g) c.b[d][h][g] = gather4(B, idx[d][h], N, n0 + 64 * g, VEC);
             }
     };
+    auto multiply = [&](int base, const Chunk &c) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            if (base + d >= tile1) break;
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int g = 0; g < NG; ++g) {
+                    acc[g][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(c.a[d][h], c.b[d][h][g].x, acc[g][0], 0, 0, 0);
+                    acc[g][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(c.a[d][h], c.b[d][h][g].y, acc[g][1], 0, 0, 0);
+                    acc[g][2] = __builtin_amdgcn_mfma_f32_16x16x4f32(c.a[d][h], c.b[d][h][g].z, acc[g][2], 0, 0, 0);
+                    acc[g][3] = __builtin_amdgcn_mfma_f32_16x16x4f32(c.a[d][h], c.b[d][h][g].w, acc[g][3], 0, 0, 0);
+                }
+        }
+    };
 
-    const int tile0 = td.y >> 3, tile1 = td.z >> 3;
-    Stage cur, nxt;
-    fetch(tile0, cur);
-    for (int tile = tile0; tile < tile1; ++tile) {
-        if (tile + 1 < tile1) fetch(tile + 1, nxt);
-        multiply(cur);
-        if (tile + 1 < tile1) cur = nxt;
+    int idx[D][2];
+    Chunk cur, nxt;
+    load_idx(tile0, idx);
+    gather(tile0, idx, cur);
+    load_idx(tile0 + D, idx);
+    for (int base = tile0; base < tile1; base += D) {
+        const bool more = base + D < tile1;
+        if (more) {
+            gather(base + D, idx, nxt);
+            load_idx(base + 2 * D, idx);
+        }
+        multiply(base, cur);
+        if (more) cur = nxt;
     }
 
     // D layout: register r of lane l is row 4*(l/16) + r, MFMA column l%16 -> C column n0 + 64g + t
@@ -347,12 +372,17 @@ WcsrPlan wcsr_plan(const asp_handle *h, int64_t N, bool aligned) {
     if (h->b_row == 16) {
         // Section IV-C rule over the built wave widths: widest that divides N, else least padding
         static const int cand[3] = {64, 128, 256};
+        static const int env_max = [] {  // benchmarking switch only: widest wave tile to consider
+            const char *e = std::getenv("ASP_WCSR_MAX_BN");
+            return e ? std::atoi(e) : 256;
+        }();
         int best = -1;
         for (int c : cand)
-            if (N % c == 0 && c > best) best = c;
+            if (c <= env_max && N % c == 0 && c > best) best = c;
         if (best < 0) {
             int64_t best_pad = -1;
             for (int c : cand) {
+                if (c > env_max) continue;
                 int64_t pad = ceil_div(N, c) * c;
                 if (best_pad < 0 || pad < best_pad || (pad == best_pad && c > best)) {
                     best_pad = pad;
