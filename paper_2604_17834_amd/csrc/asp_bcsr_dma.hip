@@ -78,9 +78,6 @@ __device__ __forceinline__ void dma16_to_lds(const void *gptr, uint32_t lds_base
                  : "memory", "m0");
 }
 __device__ __forceinline__ void dma16_to_lds(const void *sbase, uint32_t voff, uint32_t lds_base) {
-#ifdef ASP_DBG_NOLOAD
-    return;
-#endif
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(uniform_ptr(sbase)),
                  "s"(uniform32(lds_base))
                  : "memory", "m0");
@@ -91,9 +88,6 @@ __device__ __forceinline__ uint32_t lds_offset(const void *p) { return (uint32_t
 // plain stores were measured ~10 % slower end to end because the written lines displace B slabs in L2
 // (a store-only kernel with this access pattern is faster with plain stores; the product is not).
 __device__ __forceinline__ void store_c16(uint16_t *dst, uint4 v) {
-#ifdef ASP_DBG_NOSTORE
-    if (v.x != 0x12345678u) return;
-#endif
     typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
     u32x4 w = {v.x, v.y, v.z, v.w};
     __builtin_nontemporal_store(w, (u32x4 *)dst);
@@ -156,7 +150,7 @@ struct XcdRuns {
 
 // rank_info[r] = {block-row, first stored block, number of stored blocks, 0} of the r-th heaviest block-row
 template <int BR, int BN, int WM, int WN, int NS>
-__global__ __launch_bounds__(WM *WN * 64, 2) void bcsr_spmm_dma_kernel(
+__global__ __launch_bounds__(WM *WN * 64, (BR / WM) * (BN / WN) > 8192 ? 1 : 2) void bcsr_spmm_dma_kernel(
     const int4 *__restrict__ rank_info, const int32_t *__restrict__ block_col_idx,
     const uint16_t *__restrict__ a_packed, const uint16_t *__restrict__ B, uint16_t *__restrict__ C, int M, int K,
     int N, int n_brows, int n_tiles, int group_n, XcdRuns runs) {
@@ -204,16 +198,14 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void bcsr_spmm_dma_kernel(
     const uint32_t a_voff = (uint32_t)(wave * 1024 + lane * 16);
     const uint32_t lds0 = lds_offset(lds);
 
-    // ---- tile parameters: two slots, the tile being multiplied and the one after it -------------
+    // ---- tile parameters ------------------------------------------------------------------------
+    // (kept in named scalars: arrays indexed at run time would be placed in LDS or scratch by the
+    // compiler, and everything read back from there counts as lane-varying)
     struct Tile {
-        int br, n0, blk0, T;
-        int bcol0;  // block column of the tile's first stored block (loaded early, see issue_slice)
+        int br, n0, T;  // block-row, first column, number of K slices
+        int blk0;       // first stored block of the block-row
+        int bcol0;      // block column of that block (loaded early: no step waits for a dependent load)
     };
-    // (named objects and selects instead of arrays indexed at run time: such arrays would be placed in
-    // LDS or scratch, and everything read back from there counts as lane-varying for the compiler)
-    Tile tile0, tile1;
-    uint32_t b_voff0[Cfg::B_LPW], b_voff1[Cfg::B_LPW];  // per-lane byte offsets of the B loads within a slice
-    auto tile_T = [&](int slot) { return slot ? tile1.T : tile0.T; };
     auto decode = [&](int idx, Tile &t, uint32_t (&voff)[Cfg::B_LPW]) {
         const int per_group = group_n * n_brows;
         const int grp = idx / per_group, in_grp = idx - grp * per_group;
@@ -232,80 +224,91 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void bcsr_spmm_dma_kernel(
         for (int i = 0; i < Cfg::B_LPW; ++i) {
             int col = t.n0 + 8 * b_chunk[i];
             col = col < N ? col : N - 8;  // chunks past N only feed columns that are never stored
-            voff[i] = (uint32_t)(((int64_t)b_row_in_slice[i] * N + col) * 2);
+            voff[i] = (uint32_t)(((int64_t)b_row_in_slice[i] * N + col) * 2);  // byte offset inside a slice of B
         }
     };
 
     // ---- the slice stream ---------------------------------------------------------------------------
-    // cur: slot of the tile being multiplied.  The prefetch cursor (pf_slot, pf_t) is the next slice to
-    // request; it is in the current tile (pf_ahead = 0) or in the next one (pf_ahead = 1), never further.
+    // cur_t is the tile being multiplied, nxt_t the one after it (if have_next).  The prefetch cursor is
+    // the next slice to request; it carries its own copy of what it needs (pf_*), sits in the current tile
+    // or, once that is fully requested, in the next one (pf_in_next), never further.
     // Buffers buf_c, buf_c+1, .. (mod NS) hold the `inflight` slices requested but not yet multiplied.
     // issued counts the vector-memory operations of this wave; mark[b] is its value right after the
     // loads into buffer b were issued, so issued - mark[b] operations may remain outstanding when the
     // content of b is needed (the counter retires in order).
-    int cur = 0, have_next = 0;
-    int pf_slot = 0, pf_t = 0, pf_ahead = 0;
-    // block column of the block the cursor is in, and of the block after it: an index is always loaded
-    // one block before it is needed, so that no step waits for a dependent scalar load
-    int pf_bcol = 0, pf_bcol_next = 0;
+    Tile cur_t, nxt_t;
+    uint32_t nxt_voff[Cfg::B_LPW], pf_voff[Cfg::B_LPW];
+    int have_next = 0;
+    int pf_T = 0, pf_t = 0, pf_blk = 0, pf_s = 0, pf_in_next = 0;
+    int pf_bcol = 0, pf_bcol_next = 0;  // block column of the cursor's block and of the block after it
     int buf_c = 0, inflight = 0;
     int issued = 0, mark0 = 0, mark1 = 0, mark2 = 0;
     auto mark_of = [&](int b) { return b == 0 ? mark0 : (b == 1 ? mark1 : mark2); };
-
-    decode(idx_cur, tile0, b_voff0);
-    tile1 = tile0;
+    auto cursor_enter = [&](const Tile &t, const uint32_t (&voff)[Cfg::B_LPW]) {
+        pf_T = t.T;
+        pf_t = 0;
+        pf_blk = t.blk0;
+        pf_s = 0;
+        pf_bcol_next = t.bcol0;
 #pragma unroll
-    for (int i = 0; i < Cfg::B_LPW; ++i) b_voff1[i] = b_voff0[i];
+        for (int i = 0; i < Cfg::B_LPW; ++i) pf_voff[i] = voff[i];
+    };
+
+    decode(idx_cur, cur_t, nxt_voff);
+    cursor_enter(cur_t, nxt_voff);
+    nxt_t = cur_t;
     if (idx_cur + stride < run_end) {
         have_next = 1;
-        decode(idx_cur + stride, tile1, b_voff1);
+        decode(idx_cur + stride, nxt_t, nxt_voff);
     }
 
-    auto issue_slice = [&](const Tile &tl, const uint32_t (&voff)[Cfg::B_LPW], int t, int buf) {
-        const int p = tl.blk0 + t / Cfg::SPB, s = t % Cfg::SPB;
+    // request the cursor's slice into ring buffer buf and move the cursor on
+    auto issue_slice = [&](int buf) {
         const uint32_t stage = lds0 + buf * Cfg::STAGE;
-        const uint8_t *abase = (const uint8_t *)(a_packed + (int64_t)p * (BR * BR) + (int64_t)s * (BR * KS));
+        // the blocks of a block-row, and the slices of a block, are consecutive in a_packed
+        const uint8_t *abase = (const uint8_t *)a_packed + ((int64_t)pf_blk * (BR * BR) + pf_s * (BR * KS)) * 2;
 #pragma unroll
         for (int i = 0; i < Cfg::A_LPW; ++i)
             dma16_to_lds(abase + i * NW * 1024, a_voff, stage + (i * NW + wave) * 1024);
-        if (s == 0) {
-            pf_bcol = t == 0 ? tl.bcol0 : pf_bcol_next;
-            if (t + Cfg::SPB < tl.T) pf_bcol_next = __builtin_amdgcn_readfirstlane(block_col_idx[p + 1]);
+        if (pf_s == 0) {
+            pf_bcol = pf_bcol_next;
+            if (pf_t + Cfg::SPB < pf_T) pf_bcol_next = __builtin_amdgcn_readfirstlane(block_col_idx[pf_blk + 1]);
         }
-        const int krow0 = pf_bcol * BR + s * KS;
+        const int krow0 = pf_bcol * BR + pf_s * KS;
         const uint8_t *bbase = (const uint8_t *)(B + (int64_t)krow0 * N);
         if (krow0 + KS <= K) {
 #pragma unroll
             for (int i = 0; i < Cfg::B_LPW; ++i)
-                dma16_to_lds(bbase, voff[i], stage + Cfg::A_STAGE + (i * NW + wave) * 1024);
+                dma16_to_lds(bbase, pf_voff[i], stage + Cfg::A_STAGE + (i * NW + wave) * 1024);
         } else {
             // the slice crosses K: rows past K are read from row K-1, they meet the zero padding of A
 #pragma unroll
             for (int i = 0; i < Cfg::B_LPW; ++i) {
                 int krow = krow0 + b_row_in_slice[i];
                 int back = krow < K ? 0 : krow - (K - 1);
-                dma16_to_lds(bbase + voff[i] - (int64_t)back * N * 2, stage + Cfg::A_STAGE + (i * NW + wave) * 1024);
+                dma16_to_lds(bbase + pf_voff[i] - (int64_t)back * N * 2, stage + Cfg::A_STAGE + (i * NW + wave) * 1024);
             }
+        }
+        ++pf_t;
+        if (++pf_s == Cfg::SPB) {
+            pf_s = 0;
+            ++pf_blk;
         }
     };
     // request the next slice of the stream, if there is one within reach; returns whether it did
     auto prefetch_one = [&]() -> bool {
-        if (pf_t >= tile_T(pf_slot)) {  // this tile is fully requested: step into the next one
-            if (pf_ahead != 0 || !have_next) return false;
-            pf_slot ^= 1;
-            pf_ahead = 1;
-            pf_t = 0;
-            if (tile_T(pf_slot) == 0) return false;
+        if (pf_t >= pf_T) {  // this tile is fully requested: step into the next one
+            if (pf_in_next || !have_next || nxt_t.T == 0) return false;
+            cursor_enter(nxt_t, nxt_voff);
+            pf_in_next = 1;
         }
         int buf = buf_c + inflight;
         buf = buf >= NS ? buf - NS : buf;
-        if (pf_slot == 0) issue_slice(tile0, b_voff0, pf_t, buf);
-        else issue_slice(tile1, b_voff1, pf_t, buf);
+        issue_slice(buf);
         issued += LPW;
         mark0 = buf == 0 ? issued : mark0;
         mark1 = buf == 1 ? issued : mark1;
         mark2 = buf == 2 ? issued : mark2;
-        ++pf_t;
         ++inflight;
         return true;
     };
@@ -322,34 +325,37 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void bcsr_spmm_dma_kernel(
         else wait_vmcnt_and_lds<0>();
     };
 
-    auto compute_slice = [&](f32x16 (&acc)[MT][NTL], int buf) {
+    // MFMA operand fragments of one 16-wide k step of the slice in ring buffer buf
+    struct Frags {
+        bf16x8 a[MT], b[NTL];
+    };
+    auto load_frags = [&](int buf, int kk, Frags &f) {
         const uint8_t *sa = lds + buf * Cfg::STAGE, *sb = sa + Cfg::A_STAGE;
 #pragma unroll
-        for (int kk = 0; kk < Cfg::KK; ++kk) {
-            bf16x8 af[MT], bfr[NTL];
+        for (int i = 0; i < MT; ++i) f.a[i] = *(const bf16x8 *)(sa + (kk * (BR / 32) + wm * MT + i) * 1024 + a_off);
 #pragma unroll
-            for (int i = 0; i < MT; ++i)
-                af[i] = *(const bf16x8 *)(sa + (kk * (BR / 32) + wm * MT + i) * 1024 + a_off);
-#pragma unroll
-            for (int j = 0; j < NTL; ++j) {
-                const uint8_t *p0 = sb + kk * 16 * Cfg::B_ROW + b_off[j];
-                short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3))) *)(p0));
-                short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (short4v __attribute__((address_space(3))) *)(p0 + 4 * Cfg::B_ROW));
-                short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                bfr[j] = __builtin_bit_cast(bf16x8, both);
-            }
-#pragma unroll
-            for (int i = 0; i < MT; ++i)
-#pragma unroll
-                for (int j = 0; j < NTL; ++j)
-                    // operands swapped: D[n][m] = sum_k B[k][n] * A[m][k]
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < NTL; ++j) {
+            const uint8_t *p0 = sb + kk * 16 * Cfg::B_ROW + b_off[j];
+            short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3))) *)(p0));
+            short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (short4v __attribute__((address_space(3))) *)(p0 + 4 * Cfg::B_ROW));
+            short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            f.b[j] = __builtin_bit_cast(bf16x8, both);
         }
     };
+    auto multiply = [&](f32x16 (&acc)[MT][NTL], const Frags &f) {
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NTL; ++j)
+                // operands swapped: D[n][m] = sum_k B[k][n] * A[m][k]
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
+    };
+    static_assert(Cfg::KK == 2, "the step below is written for two k steps per slice");
+    const bool k_aligned = K % BR == 0;  // then no slice reaches past row K of B
 
     for (;;) {
-        const Tile tc = cur ? tile1 : tile0;
+        const Tile tc = cur_t;
         // (re)fill the ring up to NS-1 slices: the buffer behind buf_c may still be read as the previous
         // tile's staging area until the next barrier
         while (inflight < NS - 1 && prefetch_one()) {
@@ -365,17 +371,52 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void bcsr_spmm_dma_kernel(
         ASP_STAMP(1);
         for (int t = 0; t < tc.T; ++t) {
             ASP_STAMP(2);
-            wait_outstanding(issued - mark_of(buf_c));  // this wave's part of the slice in buf_c has landed
+            // Steady state: the NS-1 slices t .. t+NS-2 are in flight or landed, no store sits between them
+            // (the previous tile's stores are older than slice NS-1), and the cursor is inside this tile at
+            // slice t+NS-1.  Then the wait is a constant and the request code is straight-line.
+            const bool steady = k_aligned && t >= NS - 1 && t + NS - 1 < tc.T && inflight == NS - 1 && !pf_in_next;
+            if (steady) wait_vmcnt_and_lds<(NS - 2) * LPW>();
+            else wait_outstanding(issued - mark_of(buf_c));  // this wave's part of the slice in buf_c has landed
             ASP_STAMP(3);
-            barrier_no_fence();                      // everybody's part has; the buffer behind buf_c is free
+            barrier_no_fence();  // everybody's part has landed; the buffer behind buf_c is free
             ASP_STAMP(4);
-            while (inflight < NS && prefetch_one()) {
+            Frags f0, f1;
+            load_frags(buf_c, 0, f0);  // LDS reads first: their latency runs under the request code below
+            if (steady) {
+                const int buf = buf_c == 0 ? NS - 1 : buf_c - 1;
+                const uint32_t stage = lds0 + buf * Cfg::STAGE;
+                const uint8_t *abase = (const uint8_t *)a_packed + ((int64_t)pf_blk * (BR * BR) + pf_s * (BR * KS)) * 2;
+#pragma unroll
+                for (int i = 0; i < Cfg::A_LPW; ++i)
+                    dma16_to_lds(abase + i * NW * 1024, a_voff, stage + (i * NW + wave) * 1024);
+                if (pf_s == 0) {
+                    pf_bcol = pf_bcol_next;
+                    if (pf_t + Cfg::SPB < pf_T) pf_bcol_next = __builtin_amdgcn_readfirstlane(block_col_idx[pf_blk + 1]);
+                }
+                const uint8_t *bbase = (const uint8_t *)(B + (int64_t)(pf_bcol * BR + pf_s * KS) * N);
+#pragma unroll
+                for (int i = 0; i < Cfg::B_LPW; ++i)
+                    dma16_to_lds(bbase, pf_voff[i], stage + Cfg::A_STAGE + (i * NW + wave) * 1024);
+                issued += LPW;
+                mark0 = buf == 0 ? issued : mark0;
+                mark1 = buf == 1 ? issued : mark1;
+                mark2 = buf == 2 ? issued : mark2;
+                ++pf_t;
+                if (++pf_s == Cfg::SPB) {
+                    pf_s = 0;
+                    ++pf_blk;
+                }
+            } else {
+                while (inflight < NS && prefetch_one()) {
+                }
+                --inflight;
             }
             ASP_STAMP(5);
-            compute_slice(acc, buf_c);
+            load_frags(buf_c, 1, f1);
+            multiply(acc, f0);
+            multiply(acc, f1);
             ASP_STAMP(6);
             buf_c = buf_c + 1 == NS ? 0 : buf_c + 1;
-            --inflight;
         }
 
         // ---- tile boundary ------------------------------------------------------------------------
@@ -392,9 +433,9 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void bcsr_spmm_dma_kernel(
         wait_vmcnt_and_lds<63>();
         barrier_no_fence();
         ASP_STAMP(8);
+        const bool interior = tc.br * BR + BR <= M && tc.n0 + BN <= N;
         int sbuf = buf_c == 0 ? NS - 1 : buf_c - 1;
         uint8_t *sc = lds + sbuf * Cfg::STAGE + wave * Cfg::C_WAVE;
-        const bool interior = tc.br * BR + BR <= M && tc.n0 + BN <= N;
         const int grow0 = tc.br * BR + wm * Cfg::TM + lane / Cfg::CPR;
         const int gcol0 = tc.n0 + wn * Cfg::TN + (lane % Cfg::CPR) * 8;
         const uint8_t *scl = sc + (lane / Cfg::CPR) * Cfg::C_PITCH + (lane % Cfg::CPR) * 16;
@@ -447,22 +488,16 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void bcsr_spmm_dma_kernel(
 #endif
         if (!have_next) break;
         idx_cur += stride;
+        cur_t = nxt_t;
+        if (pf_in_next) pf_in_next = 0;          // the cursor's tile is now the current one
+        else cursor_enter(nxt_t, nxt_voff);     // the cursor never left the finished tile: it follows
         if (idx_nn < run_end) {
-            if (cur) tile1 = tnn; else tile0 = tnn;
+            nxt_t = tnn;
 #pragma unroll
-            for (int i = 0; i < Cfg::B_LPW; ++i) {
-                if (cur) b_voff1[i] = voff_nn[i]; else b_voff0[i] = voff_nn[i];
-            }
+            for (int i = 0; i < Cfg::B_LPW; ++i) nxt_voff[i] = voff_nn[i];
             have_next = 1;
         } else {
             have_next = 0;
-        }
-        cur ^= 1;
-        if (pf_ahead) {
-            pf_ahead = 0;  // the cursor's tile is now the current one
-        } else {           // the cursor never left the finished tile (its successor was empty or absent)
-            pf_slot = cur;
-            pf_t = 0;
         }
     }
 }
