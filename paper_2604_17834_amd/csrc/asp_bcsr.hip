@@ -291,7 +291,7 @@ asp_status_t bcsr_spmm_launch(const asp_handle *h, const void *B, void *C, int64
         return e && std::strcmp(e, "regstage") == 0;
     }();
     if (p.vectorized && !force_regstage && N < (1ll << 25)) {
-        if (!bcsr_dma_launch(h, B, C, N, p, stream))
+        if (!bcsr_wide_launch(h, B, C, N, p, stream) && !bcsr_dma_launch(h, B, C, N, p, stream))
             return fail(ASP_ERR_UNSUPPORTED, "no kernel for this block size / tile width");
     } else if (!p.vectorized) {  // element-wise path
         switch (h->b_row) {

@@ -37,61 +37,9 @@
 // the XCD's workgroups take tiles round-robin, which deals sorted weights evenly.
 #include <cstdlib>
 
-#include "asp_internal.h"
+#include "asp_bcsr_pipe.h"
 
 namespace asp {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(4))) short short4v;
-typedef __attribute__((ext_vector_type(8))) short short8v;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((address_space(3))) void *lds_void_ptr;
-
-// s_waitcnt vmcnt(N) lgkmcnt(0): at most N vector-memory operations (the newest ones) stay in flight,
-// every LDS access and scalar load of this wave has completed
-template <int N>
-__device__ __forceinline__ void wait_vmcnt_and_lds() {
-    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (0 << 8));
-}
-
-// Workgroup barrier without the memory fence of __syncthreads(): the fence would drain vmcnt to zero and
-// with it the slices and stores that are meant to stay in flight.  Callers wait for what they need first.
-__device__ __forceinline__ void barrier_no_fence() { __builtin_amdgcn_s_barrier(); }
-
-// global_load_lds_dwordx4: LDS[lds_base + lane*16 .. +16) = 16 bytes at this lane's source address;
-// lds_base is wave-uniform (it travels in M0).  Issued as inline assembly on purpose: for the builtin
-// form the compiler cannot tell which LDS bytes the copy writes and drains vmcnt to zero before every
-// later LDS read, which would serialise the ring.  Completion is tracked by hand.
-// Form 1: per-lane 64-bit address.  Form 2: wave-uniform 64-bit base + per-lane 32-bit byte offset.
-// The wave-uniform operands are passed through readfirstlane so that they sit in SGPRs even where the
-// compiler's divergence analysis cannot prove that they are uniform.
-__device__ __forceinline__ uint32_t uniform32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
-__device__ __forceinline__ const void *uniform_ptr(const void *p) {
-    const uint64_t v = (uint64_t)(uintptr_t)p;
-    const uint64_t lo = uniform32((uint32_t)v), hi = uniform32((uint32_t)(v >> 32));
-    return (const void *)(uintptr_t)(lo | (hi << 32));
-}
-__device__ __forceinline__ void dma16_to_lds(const void *gptr, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(uniform32(lds_base))
-                 : "memory", "m0");
-}
-__device__ __forceinline__ void dma16_to_lds(const void *sbase, uint32_t voff, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(uniform_ptr(sbase)),
-                 "s"(uniform32(lds_base))
-                 : "memory", "m0");
-}
-__device__ __forceinline__ uint32_t lds_offset(const void *p) { return (uint32_t)(uintptr_t)(lds_void_ptr)p; }
-
-// 16-byte store of finished output, marked non-temporal: C is written once and never read here, and
-// plain stores were measured ~10 % slower end to end because the written lines displace B slabs in L2
-// (a store-only kernel with this access pattern is faster with plain stores; the product is not).
-__device__ __forceinline__ void store_c16(uint16_t *dst, uint4 v) {
-    typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
-    u32x4 w = {v.x, v.y, v.z, v.w};
-    __builtin_nontemporal_store(w, (u32x4 *)dst);
-}
 
 #ifdef ASP_TRACE
 // Debug builds only: cycle stamps of one wave (workgroup ASP_TRACE_WG, thread 0) are collected in LDS
@@ -141,11 +89,6 @@ struct DmaCfg {
     static_assert(NSTORE + 2 * LPW < 64, "vmcnt is a 6-bit counter");
     // swizzle of a row's 64-byte units: rows k..k+3 of a transposing read must not share banks
     __device__ static __forceinline__ int swz(int r) { return BN >= 128 ? (r & 3) : ((r >> 1) & 1); }
-};
-
-// first tile of each XCD's run of the tile order, start[8] = number of tiles
-struct XcdRuns {
-    int start[9];
 };
 
 // rank_info[r] = {block-row, first stored block, number of stored blocks, 0} of the r-th heaviest block-row
@@ -507,9 +450,7 @@ __global__ __launch_bounds__(WM *WN * 64, (BR / WM) * (BN / WN) > 8192 ? 1 : 2) 
 // Cut the tile order into 8 runs of equal weight.  Tile weight = stored blocks of its block-row + 1
 // (the 1 stands for the epilogue).  Groups of N-tiles repeat the same sorted list of block-rows, so a
 // cut is found from the per-handle prefix sums over that list.
-static XcdRuns cut_runs(const asp_handle *h, int n_tiles, int group_n) {
-    const std::vector<int64_t> &pre = h->hb.sorted_weight_prefix;  // [n_brows + 1]
-    const int64_t nbr = h->n_brows;
+XcdRuns cut_runs(const std::vector<int64_t> &pre, int64_t nbr, int n_tiles, int group_n) {
     const int64_t rows_weight = pre[nbr];
     const int64_t n_groups = ceil_div(n_tiles, group_n);
     const int64_t total_weight = rows_weight * n_tiles;
@@ -563,7 +504,7 @@ static void launch_dma(const asp_handle *h, const void *B, void *C, int64_t N, c
     int64_t workers = (int64_t)h->n_cus * (env_wgs > 0 ? env_wgs : per_cu);
     if (workers > p.workgroups) workers = p.workgroups;
     workers = std::max<int64_t>(8, workers / 8 * 8);  // the same number of workgroups on every XCD
-    const XcdRuns runs = cut_runs(h, p.n_tiles, group_n);
+    const XcdRuns runs = cut_runs(h->hb.sorted_weight_prefix, h->n_brows, p.n_tiles, group_n);
     dim3 grid((unsigned)workers), block(WM * WN * 64);
     hipLaunchKernelGGL((bcsr_spmm_dma_kernel<BR, BN, WM, WN, NS>), grid, block, 0, stream, (const int4 *)h->d_rank_info,
                        h->d_col_idx, (const uint16_t *)h->d_values, (const uint16_t *)B, (uint16_t *)C, (int)h->m,
@@ -573,7 +514,6 @@ static void launch_dma(const asp_handle *h, const void *B, void *C, int64_t N, c
 // needs N % 8 == 0, 8 <= N < 2^25 and 16-byte aligned B and C (the caller checked)
 bool bcsr_dma_launch(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream) {
     switch (h->b_row * 1000 + p.bn) {
-        case 128512: launch_dma<128, 512, 2, 4, 3>(h, B, C, N, p, stream); return true;
         case 128256: launch_dma<128, 256, 2, 2, 3>(h, B, C, N, p, stream); return true;
         case 128128: launch_dma<128, 128, 2, 2, 3>(h, B, C, N, p, stream); return true;
         case 128064: launch_dma<128, 64, 2, 2, 3>(h, B, C, N, p, stream); return true;

@@ -1,0 +1,532 @@
+// BCSR x dense SpMM for 128x128 blocks, wide-tile kernel: 128 x 512 output tiles, one wave per SIMD.
+//
+// Why a second kernel.  With 64 x 128 wave tiles (two waves per SIMD) the multiply loop reads 6 KB of
+// operand fragments from LDS per 8 MFMAs, which needs three quarters of the LDS read bandwidth at full
+// matrix-core rate; the measured ceiling of that loop is about 1.6 PFLOP/s before any global traffic.
+// A 128 x 128 wave tile reads 8 KB per 16 MFMAs (half of the LDS bandwidth), but its 256 accumulator
+// registers leave room for only one wave per SIMD.  A lone wave issues about one instruction every
+// 5-7 cycles (measured), i.e. 4-5 instructions per 32-cycle MFMA: the loop is bound by its instruction
+// count, and everything here serves to keep that near 3 instructions per MFMA:
+//   - the K loop runs block by block, 4 slices of 32 k each, fully unrolled: the ring of four LDS
+//     buffers is walked in step with the slices of a block, so every LDS address and every M0 value is
+//     an immediate offset from a register that never changes;
+//   - the request cursor (which slice to fetch next, three slices ahead) advances by two 64-bit adds
+//     per slice; the per-block and per-tile work sits in one place of the unrolled body;
+//   - a direct-to-LDS load needs one wait state after the write of M0: the MFMA issued in between
+//     provides it;
+//   - accumulators are cleared by MFMAs (0 x 0 + 0) issued during the epilogue, when the matrix core
+//     is idle, instead of 256 register writes or a second copy of the loop with a zero input.
+//
+// Structure of a step (one 32-wide K slice of a stored block, paper Section II-C, in a ring of four
+// LDS buffers filled by direct-to-LDS loads, the role TMA plays in Section III-B):
+//   phase A   read the fragments of the slice's second k16 half from LDS | 16 MFMAs on the first half
+//   phase B   wait for the next slice's loads, one fence-free barrier, read the first-half fragments
+//             of the NEXT slice, request the slice three steps ahead | 16 MFMAs on the second half
+// so LDS reads, global requests and the barrier all sit under MFMAs issued by the same wave, and the
+// fragments of a slice's first half are carried in registers across the step (and tile) boundary.
+// After the barrier of phase B nobody reads the current slice's buffer any more: it is the ring's
+// spare buffer until the next step's barrier, and a finished tile stages its output there, without
+// an extra barrier.  Slices are requested two full steps before they are waited for.
+//
+// Tiles with no stored block are not part of the stream (their rows of C are cleared by a small
+// separate kernel).  At the end of its stream a workgroup keeps requesting the last block again (into
+// free buffers, never read), so every step issues the same loads and the wait counts are constants.
+// Scheduling, swizzling, store accounting: as in the 64 x 128 kernel.
+#include <cstdlib>
+
+#include "asp_bcsr_pipe.h"
+
+namespace asp {
+
+namespace {
+
+struct WideCfg {
+    static constexpr int BR = 128, BN = 512, KS = 32, NS = 4, NW = 4;
+    static constexpr int SPB = BR / KS;
+    static constexpr int TN = BN / NW;              // wave tile: 128 rows x 128 columns
+    static constexpr int MT = BR / 32, NTL = TN / 32;
+    static constexpr int A_STAGE = BR * KS * 2, B_ROW = BN * 2, B_STAGE = KS * B_ROW, STAGE = A_STAGE + B_STAGE;
+    static constexpr int A_LPW = A_STAGE / 1024 / NW, B_LPW = B_STAGE / 1024 / NW, LPW = A_LPW + B_LPW;
+    // epilogue: a wave stages 32 rows x 128 columns at a time, privately
+    static constexpr int C_PITCH = TN * 2 + 16, C_WAVE = 32 * C_PITCH;
+    static constexpr int CPR = TN / 8, RPI = 64 / CPR;  // 16-byte units per staged row, rows per store
+    static constexpr int NSTORE = MT * (32 / RPI);
+    static constexpr int LDS_BYTES = NS * STAGE;
+    static_assert(SPB == NS, "the ring is walked in step with the slices of a block");
+    static_assert(A_LPW == 2 && B_LPW == 8 && MT == 4 && NTL == 4, "the step below is written out for these");
+    static_assert(NW * C_WAVE <= STAGE, "epilogue staging must fit into one ring buffer");
+    static_assert(NSTORE + LPW + LPW / 2 < 64 && LPW % 2 == 0, "vmcnt is a 6-bit counter");
+    static_assert(LDS_BYTES <= 163840, "LDS of one compute unit");
+};
+
+}  // namespace
+
+// rank_info[r] = {block-row, first stored block, number of stored blocks, 0} of the r-th heaviest
+// block-row; only the first n_rows (non-empty) ones are walked.  KAL: K is a multiple of the block
+// size, so no slice of B reaches past row K.
+template <bool KAL>
+__global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
+    const int4 *__restrict__ rank_info, const int32_t *__restrict__ block_col_idx,
+    const uint16_t *__restrict__ a_packed, const uint16_t *__restrict__ B, uint16_t *__restrict__ C, int M, int K,
+    int N, int n_rows, int n_blocks, int n_tiles, int group_n, XcdRuns runs) {
+    using Cfg = WideCfg;
+    constexpr int NS = Cfg::NS, NW = Cfg::NW, KS = Cfg::KS, BR = Cfg::BR, BN = Cfg::BN, MT = Cfg::MT, NTL = Cfg::NTL;
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[Cfg::LDS_BYTES];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    // ---- this workgroup's tiles: every stride-th tile of its XCD's run ------------------------------
+    const int xcd = blockIdx.x & 7, stride = gridDim.x >> 3;
+    const int run_end = __builtin_amdgcn_readfirstlane(runs.start[xcd + 1]);
+    int idx_cur = __builtin_amdgcn_readfirstlane(runs.start[xcd]) + (blockIdx.x >> 3);
+    if (idx_cur >= run_end) return;
+
+    // ---- LDS read addresses: one register per ring buffer, everything else is an immediate ----------
+    // A fragments: lane-linear 16 bytes.  B fragments, transposing read: lane i of a 16-lane group
+    // addresses row (i/4), 4 columns at 4*(i%4); rows are XOR-swizzled in 64-byte units by (row & 3).
+    const int krow_lane = 8 * (lane >> 5) + ((lane & 15) >> 2);   // + 16*kk (+4 for the upper half)
+    const int sw = (krow_lane & 3) << 2;                           // same for krow_lane + 4 and + 16
+    const int c_lane = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);  // chunk inside the 32-column tile
+    const int sub = 8 * (lane & 1);                                // byte inside the chunk
+    const uint32_t lds0 = lds_offset(lds);
+    uint32_t a_addr[NS], b_addr[NS][NTL];
+#pragma unroll
+    for (int b = 0; b < NS; ++b) {
+        a_addr[b] = lds0 + b * Cfg::STAGE + lane * 16;
+#pragma unroll
+        for (int j = 0; j < NTL; ++j) {
+            const int c = (wave * Cfg::TN + j * 32) / 8 + c_lane;
+            b_addr[b][j] = lds0 + b * Cfg::STAGE + Cfg::A_STAGE + krow_lane * Cfg::B_ROW + ((c ^ sw) * 16) + sub;
+        }
+        // opaque to the optimiser: otherwise it folds the buffer offset back into per-use additions
+        asm volatile("" : "+v"(a_addr[b]), "+v"(b_addr[b][0]), "+v"(b_addr[b][1]), "+v"(b_addr[b][2]), "+v"(b_addr[b][3]));
+    }
+    // B source: a 1 KB region is one whole row of the slice; the i-th load of this wave fills row
+    // i*NW + wave, whose swizzle (row & 3) is the wave number for every i: lane l fetches chunk
+    // l ^ (wave << 2) so that it lands at position l.
+    const int b_chunk = lane ^ (wave << 2);
+    const uint32_t a_voff0 = (uint32_t)(wave * 1024 + lane * 16), a_voff1 = a_voff0 + NW * 1024;
+    const int64_t row_bytes = (int64_t)N * 2;
+    const uint32_t m0_base = __builtin_amdgcn_readfirstlane((int)(lds0 + wave * 1024));
+
+    // ---- tile parameters, in named scalars: arrays or structs indexed at run time would be placed in
+    // LDS or scratch by the compiler, and everything read back from there counts as lane-varying -------
+    int c_br = 0, c_n0 = 0, c_nb = 0;                                   // tile being multiplied (nb: blocks)
+    int n_br = 0, n_n0 = 0, n_nb = 0, n_blk0 = 0, n_bcol0 = 0, have_next = 0;  // the tile after it
+    uint32_t n_col = 0;  // byte offset of this lane's 16-byte chunk inside a row of B
+    auto decode = [&](int idx, int &br, int &n0, int &nb, int &blk0, int &bcol0, uint32_t &colb) __attribute__((always_inline)) {
+        const int per_group = group_n * n_rows;
+        const int grp = idx / per_group, in_grp = idx - grp * per_group;
+        const int left = n_tiles - grp * group_n;
+        const int gw = left < group_n ? left : group_n;  // the last group may be narrower
+        const int rank = in_grp / gw, nt = grp * group_n + (in_grp - rank * gw);
+        const int4 ri = rank_info[rank];
+        br = __builtin_amdgcn_readfirstlane(ri.x);
+        blk0 = __builtin_amdgcn_readfirstlane(ri.y);
+        nb = __builtin_amdgcn_readfirstlane(ri.z);
+        bcol0 = __builtin_amdgcn_readfirstlane(block_col_idx[blk0]);
+        n0 = nt * BN;
+        int col = n0 + 8 * b_chunk;
+        col = col < N ? col : N - 8;  // chunks past N only feed columns that are never stored
+        colb = (uint32_t)col * 2;
+    };
+
+    // ---- the request cursor: block pf_b (of pf_nb) of its tile, stored block pf_blk; the slice to
+    // request next is given by the position in the unrolled loop.  The cursor's tile is the current one
+    // or (pf_in_next) the next one, never further: it runs three slices ahead and a tile has >= 4. ------
+    int pf_nb = 0, pf_b = 0, pf_blk = 0, pf_in_next = 0;
+    int pf_bcol = 0;      // block column of block pf_blk
+    int pf_bcol_ld = 0;   // block column of stored block pf_blk + 1 (loaded one block early)
+    uint32_t pf_voff[Cfg::B_LPW];     // per-lane byte offsets of the 8 rows this wave loads of a slice of B
+    const uint8_t *pf_abase = nullptr; // next A slice to request
+    const uint8_t *pf_bbase = nullptr; // first row of B of the next slice to request
+    auto cursor_set_tile = [&](uint32_t colb) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < Cfg::B_LPW; ++i) pf_voff[i] = colb + (uint32_t)(i * NW + wave) * (uint32_t)row_bytes;
+    };
+    auto cursor_set_block = [&]() __attribute__((always_inline)) {
+#ifdef ASP_EXP_HOTDMA
+        pf_abase = (const uint8_t *)a_packed + (int64_t)(pf_blk & 1) * (BR * BR * 2);
+        pf_bbase = (const uint8_t *)B + (int64_t)(pf_bcol & 1) * BR * row_bytes;
+#else
+        pf_abase = (const uint8_t *)a_packed + (int64_t)pf_blk * (BR * BR * 2);
+        pf_bbase = (const uint8_t *)B + (int64_t)pf_bcol * BR * row_bytes;
+#endif
+        int nb_ = pf_blk + 1;
+        nb_ = nb_ < n_blocks ? nb_ : n_blocks - 1;
+        pf_bcol_ld = __builtin_amdgcn_readfirstlane(block_col_idx[nb_]);
+    };
+    // once per block, before its slice 0 is requested
+    auto cursor_next_block = [&]() __attribute__((always_inline)) {
+        ++pf_b;
+        if (pf_b < pf_nb) {
+            ++pf_blk;
+            pf_bcol = pf_bcol_ld;
+        } else if (have_next && !pf_in_next) {
+            pf_in_next = 1;
+            pf_nb = n_nb;
+            pf_b = 0;
+            pf_blk = n_blk0;
+            pf_bcol = n_bcol0;
+            cursor_set_tile(n_col);
+        } else {
+            pf_b = pf_nb - 1;  // end of the stream: the same block again
+        }
+        pf_blk = __builtin_amdgcn_readfirstlane(pf_blk);
+        pf_bcol = __builtin_amdgcn_readfirstlane(pf_bcol);
+        cursor_set_block();
+    };
+
+    // MFMA operand fragments of one 16-wide k step
+    struct Frags {
+        bf16x8 a[MT], b[NTL];
+    };
+    auto load_a = [&](int buf, int kk, Frags &f) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+            f.a[i] = *(const bf16x8 __attribute__((address_space(3))) *)(a_addr[buf] + (kk * MT + i) * 1024);
+    };
+    auto load_b = [&](int buf, int kk, Frags &f, int j) __attribute__((always_inline)) {
+        const uint32_t p0 = b_addr[buf][j] + kk * 16 * Cfg::B_ROW;
+        short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3))) *)(p0));
+        short4v hi =
+            __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3))) *)(p0 + 4 * Cfg::B_ROW));
+        short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        f.b[j] = __builtin_bit_cast(bf16x8, both);
+    };
+    // The 256 accumulators fill the accumulation register file completely.  The MFMAs are written as
+    // inline assembly with the accumulator tied to those registers, and there is exactly one copy of the
+    // multiply loop: left to itself, or given several variants of the loop body to merge, the register
+    // allocator moves accumulators between the register files or spills all of them at every merge.
+    // Operands are swapped: D[n][m] = sum_k B[k][n] * A[m][k], so a lane ends with 4 adjacent columns.
+    // The compiler does not see MFMAs here, so the wait states between the last MFMA of a tile and the
+    // first read of its result are provided by hand (mfma_drain).
+    f32x16 acc[MT][NTL];
+#define ASP_MFMA(f, q) \
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc[(q) / NTL][(q) % NTL]) : "v"(f.b[(q) % NTL]), "v"(f.a[(q) / NTL]))
+    // the same with a direct-to-LDS load behind it: M0 = LDS destination of the wave's 1 KB region, then
+    // the MFMA (the wait state the load needs after the write of M0), then the load of 16 bytes per lane
+    // from sbase + voff
+#ifdef ASP_EXP_NODMA
+#define ASP_DMA_TEXT ""
+#else
+#define ASP_DMA_TEXT "\n\tglobal_load_lds_dwordx4 %5, %6"
+#endif
+#define ASP_MFMA_DMA(f, q, region_off, voff, sbase)                                                              \
+    asm volatile("s_add_u32 m0, %3, %4\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" ASP_DMA_TEXT \
+                 : "+a"(acc[(q) / NTL][(q) % NTL])                                                               \
+                 : "v"(f.b[(q) % NTL]), "v"(f.a[(q) / NTL]), "s"(m0_base), "i"(region_off), "v"(voff),          \
+                   "s"(uniform_ptr(sbase))                                                                       \
+                 : "memory", "scc")
+    // acc[i][j] = 0 x 0 + 0: clears a finished tile's accumulators on the matrix core, which is idle
+    // during the epilogue anyway (256 register writes would cost more than a K slice)
+    // (the compiler may set up the zero operand right in front of the first clear and knows nothing of
+    // the wait states an MFMA needs after a vector-ALU write of its operands: they are part of the asm)
+    const bf16x8 zero_frag = __builtin_bit_cast(bf16x8, short8v{0, 0, 0, 0, 0, 0, 0, 0});
+    auto mfma_clear = [&](int i, int j) __attribute__((always_inline)) {
+        asm volatile("s_nop 3\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "+a"(acc[i][j]) : "v"(zero_frag));
+    };
+    auto mfma_drain = [&]() __attribute__((always_inline)) { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); };
+#define ASP_FENCE() __builtin_amdgcn_sched_barrier(0)
+#ifdef ASP_EXP_NOBARRIER
+#define ASP_EXP_BARRIER() do {} while (0)
+#else
+#define ASP_EXP_BARRIER() barrier_no_fence()
+#endif
+
+    // B row i*NW + wave of the slice at pf_bbase.  Not KAL: rows past K are read from row K-1 (they meet
+    // the zero padding of A's last block column); s = slice inside the block.
+#define ASP_B_VOFF(s, i) \
+    (KAL ? pf_voff[i] : pf_voff[0] + (uint32_t)((((s) * KS + (i) * NW + wave) < K - pf_bcol * BR ? ((s) * KS + (i) * NW) : K - 1 - pf_bcol * BR - wave)) * (uint32_t)row_bytes)
+#define ASP_B_BASE(s) (KAL ? pf_bbase : pf_bbase - (int64_t)(s) * KS * row_bytes)
+
+    // ---- one step: slice S of a block, in ring buffer S.  The instruction order is fixed by hand
+    // (nothing moves across a fence).  HI: the previous tile's stores may still be outstanding. ---------
+    Frags f0, f1;
+    int vm_hi = 0;  // steps for which a tile's stores are still younger than the slice waited for
+    // One phase: 16 MFMAs on fragments F (q = 4*i + j uses a[i], b[j]) while the fragments G of the next
+    // phase are read from ring buffer GB, k half GK -- in the order in which they will be needed, one
+    // or two reads per MFMA, so that the four waves' LDS traffic is spread over the phase instead of
+    // arriving as one 32 KB burst that blocks the waves' issue -- and five loads of the request go out.
+#ifdef ASP_EXP_NOLDS
+#define ASP_LOAD_A1(GB, GK, G, i) (void)0
+#define ASP_LOAD_B1(GB, GK, G, j) (void)0
+#else
+#define ASP_LOAD_A1(GB, GK, G, i) \
+    G.a[i] = *(const bf16x8 __attribute__((address_space(3))) *)(a_addr[GB] + ((GK) * MT + (i)) * 1024)
+#define ASP_LOAD_B1(GB, GK, G, j) load_b(GB, GK, G, j)
+#endif
+#define ASP_PHASE(F, G, GB, GK, R0, R1, R2, R3, R4, EXTRA)                                       \
+    do {                                                                                         \
+        ASP_MFMA(F, 0);                                                                          \
+        ASP_FENCE();                                                                             \
+        ASP_LOAD_B1(GB, GK, G, 0);                                                                    \
+        ASP_LOAD_A1(GB, GK, G, 0);                                                               \
+        ASP_FENCE();                                                                             \
+        ASP_MFMA(F, 1);                                                                          \
+        ASP_FENCE();                                                                             \
+        ASP_LOAD_B1(GB, GK, G, 1);                                                                    \
+        ASP_FENCE();                                                                             \
+        ASP_MFMA(F, 2);                                                                          \
+        ASP_FENCE();                                                                             \
+        ASP_LOAD_B1(GB, GK, G, 2);                                                                    \
+        ASP_FENCE();                                                                             \
+        ASP_MFMA(F, 3);                                                                          \
+        ASP_FENCE();                                                                             \
+        ASP_LOAD_B1(GB, GK, G, 3);                                                                    \
+        EXTRA;                                                                                   \
+        ASP_FENCE();                                                                             \
+        ASP_MFMA(F, 4);                                                                          \
+        ASP_FENCE();                                                                             \
+        ASP_LOAD_A1(GB, GK, G, 1);                                                               \
+        ASP_FENCE();                                                                             \
+        R0(F, 5);                                                                                \
+        ASP_MFMA(F, 6);                                                                          \
+        R1(F, 7);                                                                                \
+        ASP_MFMA(F, 8);                                                                          \
+        ASP_FENCE();                                                                             \
+        ASP_LOAD_A1(GB, GK, G, 2);                                                               \
+        ASP_FENCE();                                                                             \
+        R2(F, 9);                                                                                \
+        ASP_MFMA(F, 10);                                                                         \
+        R3(F, 11);                                                                               \
+        ASP_MFMA(F, 12);                                                                         \
+        ASP_FENCE();                                                                             \
+        ASP_LOAD_A1(GB, GK, G, 3);                                                               \
+        ASP_FENCE();                                                                             \
+        R4(F, 13);                                                                               \
+        ASP_MFMA(F, 14);                                                                         \
+        ASP_MFMA(F, 15);                                                                         \
+        ASP_FENCE();                                                                             \
+    } while (0)
+#define ASP_RQ_A0(F, q) ASP_MFMA_DMA(F, q, tb_ * Cfg::STAGE, a_voff0, pf_abase)
+#define ASP_RQ_A1(F, q) ASP_MFMA_DMA(F, q, tb_ * Cfg::STAGE + NW * 1024, a_voff1, pf_abase)
+#ifdef ASP_EXP_FEWB
+#define ASP_RQ_B(F, q, i)                                                                                          \
+    do {                                                                                                           \
+        if ((i) < ASP_EXP_FEWB)                                                                                    \
+            ASP_MFMA_DMA(F, q, tb_ * Cfg::STAGE + Cfg::A_STAGE + (i) * NW * 1024, ASP_B_VOFF(rs_, i), ASP_B_BASE(rs_)); \
+        else                                                                                                       \
+            ASP_MFMA(F, q);                                                                                        \
+    } while (0)
+#else
+#define ASP_RQ_B(F, q, i) \
+    ASP_MFMA_DMA(F, q, tb_ * Cfg::STAGE + Cfg::A_STAGE + (i) * NW * 1024, ASP_B_VOFF(rs_, i), ASP_B_BASE(rs_))
+#endif
+#define ASP_RQ_B0(F, q) ASP_RQ_B(F, q, 0)
+#define ASP_RQ_B1(F, q) ASP_RQ_B(F, q, 1)
+#define ASP_RQ_B2(F, q) ASP_RQ_B(F, q, 2)
+#define ASP_RQ_B3(F, q) ASP_RQ_B(F, q, 3)
+#define ASP_RQ_B4(F, q) ASP_RQ_B(F, q, 4)
+#define ASP_RQ_B5(F, q) ASP_RQ_B(F, q, 5)
+#define ASP_RQ_B6(F, q) ASP_RQ_B(F, q, 6)
+#define ASP_RQ_B7(F, q) ASP_RQ_B(F, q, 7)
+#ifdef ASP_EXP_FEWB
+#define ASP_VM_LO (ASP_EXP_FEWB == 0 ? 3 : (ASP_EXP_FEWB <= 3 ? 2 + ASP_EXP_FEWB + 2 + ASP_EXP_FEWB : 2 + ASP_EXP_FEWB + 5))
+#else
+#define ASP_VM_LO (Cfg::LPW + Cfg::LPW / 2)
+#endif
+#define ASP_WIDE_STEP(S, HI_POSSIBLE)                                                                              \
+    do {                                                                                                           \
+        constexpr int nb_ = ((S) + 1) % NS, tb_ = ((S) + 3) % NS; /* tb_: free since the previous barrier */      \
+        constexpr int rs_ = ((S) + 3) % NS;                        /* slice of its block that is requested */      \
+        /* ---- phase A: first k half | fragments of the second half, first half of the request ---- */           \
+        /* (once per block, before its slice 0 is requested, the cursor moves on to the next block) */            \
+        ASP_PHASE(f0, f1, S, 1, ASP_RQ_A0, ASP_RQ_A1, ASP_RQ_B0, ASP_RQ_B1, ASP_RQ_B2,                             \
+                  if (rs_ == 0) cursor_next_block());                                                              \
+        /* ---- phase B: second k half | fragments of the next slice's first half, rest of the request ---- */    \
+        /* this wave's part of the next slice has landed (all but the newest one and a half requests and, */     \
+        /* for two steps after an interior tile, its stores may be outstanding); f1 is complete           */     \
+        if (HI_POSSIBLE && vm_hi > 0) wait_vmcnt_and_lds<Cfg::NSTORE + ASP_VM_LO>();                               \
+        else wait_vmcnt_and_lds<ASP_VM_LO>();                                                                      \
+        ASP_EXP_BARRIER(); /* everybody's part has landed, nobody reads buffer S any more */                      \
+        ASP_FENCE();                                                                                               \
+        ASP_PHASE(f1, f0, nb_, 0, ASP_RQ_B3, ASP_RQ_B4, ASP_RQ_B5, ASP_RQ_B6, ASP_RQ_B7, (void)0);                 \
+        pf_abase += Cfg::A_STAGE;                                                                                  \
+        pf_bbase += KS * row_bytes;                                                                                \
+        if (HI_POSSIBLE) vm_hi = vm_hi > 0 ? vm_hi - 1 : 0;                                                        \
+        ASP_FENCE();                                                                                               \
+    } while (0)
+
+    // ---- start of the stream: three slices requested, first-half fragments of slice 0 in registers ---
+    {
+        int blk0, bcol0;
+        uint32_t colb;
+        decode(idx_cur, c_br, c_n0, c_nb, blk0, bcol0, colb);
+        pf_nb = c_nb;
+        pf_blk = blk0;
+        pf_bcol = bcol0;
+        cursor_set_tile(colb);
+        cursor_set_block();
+        if (idx_cur + stride < run_end) {
+            have_next = 1;
+            decode(idx_cur + stride, n_br, n_n0, n_nb, n_blk0, n_bcol0, n_col);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NTL; ++j) {
+            const f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            acc[i][j] = z;
+        }
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s) {
+        dma16_to_lds(pf_abase, a_voff0, m0_base + s * Cfg::STAGE);
+        dma16_to_lds(pf_abase, a_voff1, m0_base + s * Cfg::STAGE + NW * 1024);
+#pragma unroll
+        for (int i = 0; i < Cfg::B_LPW; ++i)
+            dma16_to_lds(ASP_B_BASE(s), ASP_B_VOFF(s, i), m0_base + s * Cfg::STAGE + Cfg::A_STAGE + i * NW * 1024);
+        pf_abase += Cfg::A_STAGE;
+        pf_bbase += KS * row_bytes;
+    }
+    wait_vmcnt_and_lds<2 * Cfg::LPW>();
+    barrier_no_fence();
+    load_a(0, 0, f0);
+#pragma unroll
+    for (int j = 0; j < NTL; ++j) load_b(0, 0, f0, j);
+
+    for (;;) {
+        // (in the first two steps of a tile the stores of the previous tile are younger than the slice
+        // waited for; one copy of the loop only, see above)
+        for (int blk = 0; blk < c_nb; ++blk) {
+            ASP_WIDE_STEP(0, true);
+            ASP_WIDE_STEP(1, true);
+            ASP_WIDE_STEP(2, false);
+            ASP_WIDE_STEP(3, false);
+        }
+
+        // ---- tile boundary ------------------------------------------------------------------------
+        mfma_drain();
+        // parameters of the tile after the next one: requested now, needed after the epilogue
+        const int idx_nn = idx_cur + 2 * stride;
+        int nn_br = 0, nn_n0 = 0, nn_nb = 0, nn_blk0 = 0, nn_bcol0 = 0;
+        uint32_t nn_col = 0;
+        if (idx_nn < run_end) decode(idx_nn, nn_br, nn_n0, nn_nb, nn_blk0, nn_bcol0, nn_col);
+
+        // the buffer of the slice just finished (always the last one of the ring) is the spare one
+        // until the next barrier
+        const bool interior = c_br * BR + BR <= M && c_n0 + BN <= N;
+        uint8_t *sc = lds + (NS - 1) * Cfg::STAGE + wave * Cfg::C_WAVE;
+        const int grow0 = c_br * BR + lane / Cfg::CPR;
+        const int gcol0 = c_n0 + wave * Cfg::TN + (lane % Cfg::CPR) * 8;
+        const uint8_t *scl = sc + (lane / Cfg::CPR) * Cfg::C_PITCH + (lane % Cfg::CPR) * 16;
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+            // fp32 -> bf16 (round to nearest even); lane holds row (lane & 31), 4 adjacent columns per q
+#pragma unroll
+            for (int j = 0; j < NTL; ++j) {
+                f32x16 a = acc[i][j];
+                asm volatile("" : "+v"(a));  // the copy sits in vector registers before the clear overwrites
+                mfma_clear(i, j);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    f32x4 v = {a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]};
+                    bf16x4 hv = __builtin_convertvector(v, bf16x4);
+                    *(bf16x4 *)(sc + (lane & 31) * Cfg::C_PITCH + (j * 32 + 8 * q + 4 * (lane >> 5)) * 2) = hv;
+                }
+            }
+            // LDS is in order within a wave: the reads below see the writes above
+            uint16_t *cdst = C + (int64_t)(grow0 + i * 32) * N + gcol0;
+            if (interior) {
+#pragma unroll
+                for (int it = 0; it < 32 / Cfg::RPI; ++it) {
+                    uint4 v = *(const uint4 *)(scl + it * Cfg::RPI * Cfg::C_PITCH);
+                    store_c16(cdst + (int64_t)it * Cfg::RPI * N, v);
+                }
+            } else {
+#pragma unroll
+                for (int it = 0; it < 32 / Cfg::RPI; ++it) {
+                    uint4 v = *(const uint4 *)(scl + it * Cfg::RPI * Cfg::C_PITCH);
+                    if (grow0 + i * 32 + it * Cfg::RPI < M && gcol0 < N) store_c16(cdst + (int64_t)it * Cfg::RPI * N, v);
+                }
+            }
+            ASP_FENCE();  // keeps the pieces apart: reading all 256 accumulators at once would spill
+        }
+        if (interior) {
+            vm_hi = 2;  // exactly NSTORE stores were issued, none is waited for
+        } else {
+            // an edge tile issues a data-dependent number of stores: drain once so the counts are exact again
+            wait_vmcnt_and_lds<0>();
+            vm_hi = 0;
+        }
+
+        // ---- advance to the next tile ---------------------------------------------------------------
+        if (!have_next) break;
+        // the next step requests into the staging buffer before its own barrier: every wave must be done
+        // reading its staging area first
+        wait_vmcnt_and_lds<63>();
+        barrier_no_fence();
+        idx_cur += stride;
+        c_br = n_br;
+        c_n0 = n_n0;
+        c_nb = n_nb;
+        pf_in_next = 0;  // the cursor entered this tile three slices ago
+        if (idx_nn < run_end) {
+            n_br = nn_br;
+            n_n0 = nn_n0;
+            n_nb = nn_nb;
+            n_blk0 = nn_blk0;
+            n_bcol0 = nn_bcol0;
+            n_col = nn_col;
+            have_next = 1;
+        } else {
+            have_next = 0;
+        }
+    }
+    // the cursor's repeated requests at the end of the stream still write LDS: they must have landed
+    // before the workgroup gives its LDS back
+    wait_vmcnt_and_lds<0>();
+#undef ASP_FENCE
+#undef ASP_WIDE_STEP
+#undef ASP_MFMA
+#undef ASP_MFMA_DMA
+#undef ASP_B_VOFF
+#undef ASP_B_BASE
+}
+
+// rows of C that belong to block-rows without stored blocks (ranks n_rows .. n_brows-1)
+__global__ __launch_bounds__(256) void bcsr_clear_empty_rows_kernel(const int4 *__restrict__ rank_info, int n_rows,
+                                                                    uint16_t *__restrict__ C, int M, int N, int BR) {
+    const int br = rank_info[n_rows + blockIdx.x].x;
+    const int r0 = br * BR, r1 = r0 + BR < M ? r0 + BR : M;
+    uint4 *dst = (uint4 *)(C + (int64_t)r0 * N);           // whole rows: one contiguous span, N % 8 == 0
+    const int64_t n16 = (int64_t)(r1 - r0) * N / 8;
+    const uint4 z = {0u, 0u, 0u, 0u};
+    for (int64_t i = (int64_t)blockIdx.y * 256 + threadIdx.x; i < n16; i += (int64_t)gridDim.y * 256) dst[i] = z;
+}
+
+// needs b_row = 128, bn = 512, N % 8 == 0, 8 <= N < 2^25 and 16-byte aligned B and C (the caller checked)
+bool bcsr_wide_launch(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream) {
+    if (h->b_row != 128 || p.bn != 512) return false;
+    static const int env_group = [] {  // benchmarking switch only
+        const char *e = std::getenv("ASP_BCSR_GROUP_N");
+        return e ? std::atoi(e) : 0;
+    }();
+    int group_n = env_group > 0 ? env_group : 4;
+    if (group_n > p.n_tiles) group_n = p.n_tiles;
+    const int64_t n_rows = h->hb.n_nonempty, n_empty = h->n_brows - n_rows;
+    if (n_empty > 0) {
+        dim3 grid((unsigned)n_empty, 16), block(256);
+        hipLaunchKernelGGL(bcsr_clear_empty_rows_kernel, grid, block, 0, stream, (const int4 *)h->d_rank_info, (int)n_rows,
+                           (uint16_t *)C, (int)h->m, (int)N, 128);
+    }
+    if (n_rows == 0) return true;
+    int64_t workers = h->n_cus;  // one resident workgroup per CU: the ring takes the whole LDS
+    if (workers > n_rows * p.n_tiles) workers = n_rows * p.n_tiles;
+    workers = std::max<int64_t>(8, workers / 8 * 8);  // the same number of workgroups on every XCD
+    const XcdRuns runs = cut_runs(h->hb.sorted_weight_prefix, n_rows, p.n_tiles, group_n);
+    dim3 grid((unsigned)workers), block(256);
+    if (h->k % 128 == 0)
+        hipLaunchKernelGGL(bcsr_spmm_wide_kernel<true>, grid, block, 0, stream, (const int4 *)h->d_rank_info,
+                           h->d_col_idx, (const uint16_t *)h->d_values, (const uint16_t *)B, (uint16_t *)C, (int)h->m,
+                           (int)h->k, (int)N, (int)n_rows, (int)h->n_units, p.n_tiles, group_n, runs);
+    else
+        hipLaunchKernelGGL(bcsr_spmm_wide_kernel<false>, grid, block, 0, stream, (const int4 *)h->d_rank_info,
+                           h->d_col_idx, (const uint16_t *)h->d_values, (const uint16_t *)B, (uint16_t *)C, (int)h->m,
+                           (int)h->k, (int)N, (int)n_rows, (int)h->n_units, p.n_tiles, group_n, runs);
+    return true;
+}
+
+}  // namespace asp

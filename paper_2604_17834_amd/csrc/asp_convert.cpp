@@ -143,6 +143,7 @@ void bcsr_build_schedule(HostBcsr &b) {
     std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return len(x) > len(y); });
     b.rank_info.resize((size_t)nbr * 4);
     b.sorted_weight_prefix.assign(nbr + 1, 0);
+    b.n_nonempty = 0;
     for (int64_t r = 0; r < nbr; ++r) {
         const int32_t br = order[r];
         b.rank_info[4 * r + 0] = br;
@@ -150,6 +151,7 @@ void bcsr_build_schedule(HostBcsr &b) {
         b.rank_info[4 * r + 2] = len(br);
         b.rank_info[4 * r + 3] = 0;
         b.sorted_weight_prefix[r + 1] = b.sorted_weight_prefix[r] + len(br) + 1;
+        if (len(br) > 0) b.n_nonempty = r + 1;
     }
 }
 

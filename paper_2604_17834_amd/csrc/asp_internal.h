@@ -36,6 +36,7 @@ struct HostBcsr {
     // prefix sums of their tile weights (stored blocks + 1) in that order
     std::vector<int32_t> rank_info;            // [n_brows][4]
     std::vector<int64_t> sorted_weight_prefix; // [n_brows + 1]
+    int64_t n_nonempty = 0;                    // block-rows with at least one stored block (they come first)
 };
 
 struct HostWcsr {
@@ -92,6 +93,7 @@ struct BcsrPlan {
 };
 BcsrPlan bcsr_plan(const asp_handle *h, int64_t N, bool aligned);
 bool bcsr_dma_launch(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream);
+bool bcsr_wide_launch(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream);
 asp_status_t bcsr_spmm_launch(const asp_handle *h, const void *B, void *C, int64_t N, hipStream_t stream);
 
 struct WcsrPlan {
