@@ -90,7 +90,7 @@ typedef struct {
     int32_t bn;          /* columns of B/C handled by one workgroup (BCSR) or one wave (WCSR) */
     int32_t n_tiles;     /* ceil(N / bn): tiles along N, the last one masked if bn does not divide N */
     int32_t vectorized;  /* 1: 16-byte row accesses (needs N*sizeof(dtype) % 16 == 0 and 16-byte aligned B, C) */
-    int64_t workgroups;  /* workgroups of the main kernel */
+    int64_t workgroups;  /* output tiles of the main kernel (one workgroup each, or the work list of its resident workgroups) */
     int64_t padded_n;    /* n_tiles * bn: width actually computed on */
 } asp_plan_t;
 

@@ -256,15 +256,26 @@ BcsrPlan bcsr_plan(const asp_handle *h, int64_t N, bool aligned) {
     BcsrPlan p;
     p.vectorized = (aligned && N % 8 == 0) ? 1 : 0;
     static const int cand[4] = {64, 128, 256, 512};
-    // 512-wide tiles are only built for 128x128 blocks and only pay when there are enough tiles per CU
-    const int ncand = (h->b_row == 128 && std::getenv("ASP_BCSR_BN512")) ? 4 : 3;
-    p.bn = p.vectorized ? choose_bn(N, cand, ncand) : 64;  // the element-wise path is only built for BN = 64
-    // benchmarking switch only: ASP_BCSR_BN forces a narrower tile (it must be one of the built widths)
+    // benchmarking switch only: ASP_BCSR_BN caps the tile width (it must be one of the built widths)
     static const int env_bn = [] {
         const char *e = std::getenv("ASP_BCSR_BN");
         return e ? std::atoi(e) : 0;
     }();
-    if (p.vectorized && (env_bn == 64 || env_bn == 128 || env_bn == 256) && env_bn < p.bn) p.bn = env_bn;
+    if (!p.vectorized) {
+        p.bn = 64;  // the element-wise path is only built for BN = 64
+    } else {
+        // 512-wide tiles (one resident workgroup per compute unit) exist for 128x128 blocks and only pay
+        // when every compute unit gets at least one tile
+        int ncand = 3;
+        if (h->b_row == 128 && N < (1ll << 25)) {
+            const int64_t cus = h->n_cus > 0 ? h->n_cus : 256;
+            const int64_t rows = h->hb.n_nonempty > 0 ? h->hb.n_nonempty : h->n_brows;
+            if (rows * ceil_div(N, 512) >= cus) ncand = 4;
+        }
+        if (env_bn == 64 || env_bn == 128 || env_bn == 256)
+            while (ncand > 1 && cand[ncand - 1] > env_bn) --ncand;
+        p.bn = choose_bn(N, cand, ncand);
+    }
     p.n_tiles = (int32_t)ceil_div(N, p.bn);
     p.workgroups = h->n_brows * p.n_tiles;
     return p;

@@ -91,7 +91,7 @@ struct DmaCfg {
     __device__ static __forceinline__ int swz(int r) { return BN >= 128 ? (r & 3) : ((r >> 1) & 1); }
 };
 
-// rank_info[r] = {block-row, first stored block, number of stored blocks, 0} of the r-th heaviest block-row
+// rank_info[r] = {block-row, first stored block, number of stored blocks, block column of the first one} of the r-th heaviest block-row
 template <int BR, int BN, int WM, int WN, int NS>
 __global__ __launch_bounds__(WM *WN * 64, (BR / WM) * (BN / WN) > 8192 ? 1 : 2) void bcsr_spmm_dma_kernel(
     const int4 *__restrict__ rank_info, const int32_t *__restrict__ block_col_idx,

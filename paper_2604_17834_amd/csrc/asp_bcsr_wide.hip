@@ -61,7 +61,7 @@ struct WideCfg {
 
 }  // namespace
 
-// rank_info[r] = {block-row, first stored block, number of stored blocks, 0} of the r-th heaviest
+// rank_info[r] = {block-row, first stored block, number of stored blocks, block column of the first one} of the r-th heaviest
 // block-row; only the first n_rows (non-empty) ones are walked.  KAL: K is a multiple of the block
 // size, so no slice of B reaches past row K.
 template <bool KAL>
@@ -125,7 +125,7 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
         br = __builtin_amdgcn_readfirstlane(ri.x);
         blk0 = __builtin_amdgcn_readfirstlane(ri.y);
         nb = __builtin_amdgcn_readfirstlane(ri.z);
-        bcol0 = __builtin_amdgcn_readfirstlane(block_col_idx[blk0]);
+        bcol0 = __builtin_amdgcn_readfirstlane(ri.w);
         n0 = nt * BN;
         int col = n0 + 8 * b_chunk;
         col = col < N ? col : N - 8;  // chunks past N only feed columns that are never stored
@@ -146,13 +146,11 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
         for (int i = 0; i < Cfg::B_LPW; ++i) pf_voff[i] = colb + (uint32_t)(i * NW + wave) * (uint32_t)row_bytes;
     };
     auto cursor_set_block = [&]() __attribute__((always_inline)) {
-#ifdef ASP_EXP_HOTDMA
-        pf_abase = (const uint8_t *)a_packed + (int64_t)(pf_blk & 1) * (BR * BR * 2);
-        pf_bbase = (const uint8_t *)B + (int64_t)(pf_bcol & 1) * BR * row_bytes;
-#else
-        pf_abase = (const uint8_t *)a_packed + (int64_t)pf_blk * (BR * BR * 2);
-        pf_bbase = (const uint8_t *)B + (int64_t)pf_bcol * BR * row_bytes;
-#endif
+        // (made scalar here, well before the requests read them: a memory instruction may read a scalar
+        // register only five wait states after a vector instruction wrote it, the compiler keeps such
+        // wave-uniform values in vector registers at times, and it does not see the loads inside the asm)
+        pf_abase = (const uint8_t *)uniform_ptr((const uint8_t *)a_packed + (int64_t)pf_blk * (BR * BR * 2));
+        pf_bbase = (const uint8_t *)uniform_ptr((const uint8_t *)B + (int64_t)pf_bcol * BR * row_bytes);
         int nb_ = pf_blk + 1;
         nb_ = nb_ < n_blocks ? nb_ : n_blocks - 1;
         pf_bcol_ld = __builtin_amdgcn_readfirstlane(block_col_idx[nb_]);
@@ -182,16 +180,16 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     struct Frags {
         bf16x8 a[MT], b[NTL];
     };
+    typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
+    typedef __attribute__((address_space(3))) short4v lds_short4v;
     auto load_a = [&](int buf, int kk, Frags &f) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < MT; ++i)
-            f.a[i] = *(const bf16x8 __attribute__((address_space(3))) *)(a_addr[buf] + (kk * MT + i) * 1024);
+        for (int i = 0; i < MT; ++i) f.a[i] = *(const lds_bf16x8 *)(uintptr_t)(a_addr[buf] + (kk * MT + i) * 1024);
     };
     auto load_b = [&](int buf, int kk, Frags &f, int j) __attribute__((always_inline)) {
         const uint32_t p0 = b_addr[buf][j] + kk * 16 * Cfg::B_ROW;
-        short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3))) *)(p0));
-        short4v hi =
-            __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3))) *)(p0 + 4 * Cfg::B_ROW));
+        short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4v *)(uintptr_t)(p0));
+        short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4v *)(uintptr_t)(p0 + 4 * Cfg::B_ROW));
         short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         f.b[j] = __builtin_bit_cast(bf16x8, both);
     };
@@ -208,13 +206,8 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     // the same with a direct-to-LDS load behind it: M0 = LDS destination of the wave's 1 KB region, then
     // the MFMA (the wait state the load needs after the write of M0), then the load of 16 bytes per lane
     // from sbase + voff
-#ifdef ASP_EXP_NODMA
-#define ASP_DMA_TEXT ""
-#else
-#define ASP_DMA_TEXT "\n\tglobal_load_lds_dwordx4 %5, %6"
-#endif
 #define ASP_MFMA_DMA(f, q, region_off, voff, sbase)                                                              \
-    asm volatile("s_add_u32 m0, %3, %4\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" ASP_DMA_TEXT \
+    asm volatile("s_add_u32 m0, %3, %4\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\tglobal_load_lds_dwordx4 %5, %6" \
                  : "+a"(acc[(q) / NTL][(q) % NTL])                                                               \
                  : "v"(f.b[(q) % NTL]), "v"(f.a[(q) / NTL]), "s"(m0_base), "i"(region_off), "v"(voff),          \
                    "s"(uniform_ptr(sbase))                                                                       \
@@ -229,11 +222,6 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     };
     auto mfma_drain = [&]() __attribute__((always_inline)) { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); };
 #define ASP_FENCE() __builtin_amdgcn_sched_barrier(0)
-#ifdef ASP_EXP_NOBARRIER
-#define ASP_EXP_BARRIER() do {} while (0)
-#else
-#define ASP_EXP_BARRIER() barrier_no_fence()
-#endif
 
     // B row i*NW + wave of the slice at pf_bbase.  Not KAL: rows past K are read from row K-1 (they meet
     // the zero padding of A's last block column); s = slice inside the block.
@@ -249,14 +237,8 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     // phase are read from ring buffer GB, k half GK -- in the order in which they will be needed, one
     // or two reads per MFMA, so that the four waves' LDS traffic is spread over the phase instead of
     // arriving as one 32 KB burst that blocks the waves' issue -- and five loads of the request go out.
-#ifdef ASP_EXP_NOLDS
-#define ASP_LOAD_A1(GB, GK, G, i) (void)0
-#define ASP_LOAD_B1(GB, GK, G, j) (void)0
-#else
-#define ASP_LOAD_A1(GB, GK, G, i) \
-    G.a[i] = *(const bf16x8 __attribute__((address_space(3))) *)(a_addr[GB] + ((GK) * MT + (i)) * 1024)
+#define ASP_LOAD_A1(GB, GK, G, i) G.a[i] = *(const lds_bf16x8 *)(uintptr_t)(a_addr[GB] + ((GK) * MT + (i)) * 1024)
 #define ASP_LOAD_B1(GB, GK, G, j) load_b(GB, GK, G, j)
-#endif
 #define ASP_PHASE(F, G, GB, GK, R0, R1, R2, R3, R4, EXTRA)                                       \
     do {                                                                                         \
         ASP_MFMA(F, 0);                                                                          \
@@ -302,18 +284,8 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     } while (0)
 #define ASP_RQ_A0(F, q) ASP_MFMA_DMA(F, q, tb_ * Cfg::STAGE, a_voff0, pf_abase)
 #define ASP_RQ_A1(F, q) ASP_MFMA_DMA(F, q, tb_ * Cfg::STAGE + NW * 1024, a_voff1, pf_abase)
-#ifdef ASP_EXP_FEWB
-#define ASP_RQ_B(F, q, i)                                                                                          \
-    do {                                                                                                           \
-        if ((i) < ASP_EXP_FEWB)                                                                                    \
-            ASP_MFMA_DMA(F, q, tb_ * Cfg::STAGE + Cfg::A_STAGE + (i) * NW * 1024, ASP_B_VOFF(rs_, i), ASP_B_BASE(rs_)); \
-        else                                                                                                       \
-            ASP_MFMA(F, q);                                                                                        \
-    } while (0)
-#else
 #define ASP_RQ_B(F, q, i) \
     ASP_MFMA_DMA(F, q, tb_ * Cfg::STAGE + Cfg::A_STAGE + (i) * NW * 1024, ASP_B_VOFF(rs_, i), ASP_B_BASE(rs_))
-#endif
 #define ASP_RQ_B0(F, q) ASP_RQ_B(F, q, 0)
 #define ASP_RQ_B1(F, q) ASP_RQ_B(F, q, 1)
 #define ASP_RQ_B2(F, q) ASP_RQ_B(F, q, 2)
@@ -322,11 +294,6 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
 #define ASP_RQ_B5(F, q) ASP_RQ_B(F, q, 5)
 #define ASP_RQ_B6(F, q) ASP_RQ_B(F, q, 6)
 #define ASP_RQ_B7(F, q) ASP_RQ_B(F, q, 7)
-#ifdef ASP_EXP_FEWB
-#define ASP_VM_LO (ASP_EXP_FEWB == 0 ? 3 : (ASP_EXP_FEWB <= 3 ? 2 + ASP_EXP_FEWB + 2 + ASP_EXP_FEWB : 2 + ASP_EXP_FEWB + 5))
-#else
-#define ASP_VM_LO (Cfg::LPW + Cfg::LPW / 2)
-#endif
 #define ASP_WIDE_STEP(S, HI_POSSIBLE)                                                                              \
     do {                                                                                                           \
         constexpr int nb_ = ((S) + 1) % NS, tb_ = ((S) + 3) % NS; /* tb_: free since the previous barrier */      \
@@ -338,13 +305,13 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
         /* ---- phase B: second k half | fragments of the next slice's first half, rest of the request ---- */    \
         /* this wave's part of the next slice has landed (all but the newest one and a half requests and, */     \
         /* for two steps after an interior tile, its stores may be outstanding); f1 is complete           */     \
-        if (HI_POSSIBLE && vm_hi > 0) wait_vmcnt_and_lds<Cfg::NSTORE + ASP_VM_LO>();                               \
-        else wait_vmcnt_and_lds<ASP_VM_LO>();                                                                      \
-        ASP_EXP_BARRIER(); /* everybody's part has landed, nobody reads buffer S any more */                      \
+        if (HI_POSSIBLE && vm_hi > 0) wait_vmcnt_and_lds<Cfg::NSTORE + Cfg::LPW + Cfg::LPW / 2>();                               \
+        else wait_vmcnt_and_lds<Cfg::LPW + Cfg::LPW / 2>();                                                                      \
+        barrier_no_fence(); /* everybody's part has landed, nobody reads buffer S any more */                      \
         ASP_FENCE();                                                                                               \
         ASP_PHASE(f1, f0, nb_, 0, ASP_RQ_B3, ASP_RQ_B4, ASP_RQ_B5, ASP_RQ_B6, ASP_RQ_B7, (void)0);                 \
-        pf_abase += Cfg::A_STAGE;                                                                                  \
-        pf_bbase += KS * row_bytes;                                                                                \
+        pf_abase = (const uint8_t *)uniform_ptr(pf_abase + Cfg::A_STAGE);                                          \
+        pf_bbase = (const uint8_t *)uniform_ptr(pf_bbase + KS * row_bytes);                                        \
         if (HI_POSSIBLE) vm_hi = vm_hi > 0 ? vm_hi - 1 : 0;                                                        \
         ASP_FENCE();                                                                                               \
     } while (0)
@@ -504,7 +471,9 @@ bool bcsr_wide_launch(const asp_handle *h, const void *B, void *C, int64_t N, co
         const char *e = std::getenv("ASP_BCSR_GROUP_N");
         return e ? std::atoi(e) : 0;
     }();
-    int group_n = env_group > 0 ? env_group : 4;
+    // two N-tiles walked together: an A block is fetched once per pair while the pair's slab of B (K x 1024)
+    // still has a chance in the 4 MB of L2 (measured: 1, 3 and 4 are 3-10 % slower on the 90 %-sparse projection)
+    int group_n = env_group > 0 ? env_group : 2;
     if (group_n > p.n_tiles) group_n = p.n_tiles;
     const int64_t n_rows = h->hb.n_nonempty, n_empty = h->n_brows - n_rows;
     if (n_empty > 0) {

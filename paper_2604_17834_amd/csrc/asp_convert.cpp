@@ -149,7 +149,7 @@ void bcsr_build_schedule(HostBcsr &b) {
         b.rank_info[4 * r + 0] = br;
         b.rank_info[4 * r + 1] = b.block_row_ptr[br];
         b.rank_info[4 * r + 2] = len(br);
-        b.rank_info[4 * r + 3] = 0;
+        b.rank_info[4 * r + 3] = len(br) > 0 ? b.block_col_idx[b.block_row_ptr[br]] : 0;  // column of its first block
         b.sorted_weight_prefix[r + 1] = b.sorted_weight_prefix[r] + len(br) + 1;
         if (len(br) > 0) b.n_nonempty = r + 1;
     }

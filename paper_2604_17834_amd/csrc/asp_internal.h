@@ -79,7 +79,7 @@ struct asp_handle {
     void *d_values = nullptr;       // BCSR: fragment-packed blocks; WCSR: canonical tiles
     int32_t *d_tasks = nullptr;     // WCSR tasks [n_tasks][4]
     int32_t *d_zero_windows = nullptr;
-    int32_t *d_rank_info = nullptr; // BCSR: [n_brows][4] = {block-row, first block, stored blocks, 0}, heaviest first
+    int32_t *d_rank_info = nullptr; // BCSR: [n_brows][4] = {block-row, first block, stored blocks, block column of the first one}, heaviest first
     int n_cus = 0;                  // compute units of the owning device
 };
 

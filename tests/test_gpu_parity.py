@@ -179,6 +179,64 @@ def test_bcsr_geometric_rows_sampled(b, sparsity):
     check_against_oracle(a, B, C, _sample_columns(1024, 256, np.random.default_rng(2)))
 
 
+
+# ---- 128 x 128 blocks with 512-wide tiles (chosen when every compute unit gets a tile) -------------------
+def _plan_bn(a, N):
+    h = asp.asp_create_from_csr("bcsr", "bf16", 128, 128, a.m, a.k, a.row_ptr, a.col_idx, a.values)
+    try:
+        return asp.asp_plan_spmm(h, N).bn
+    finally:
+        asp.asp_destroy(h)
+
+
+@pytest.mark.parametrize("m,k,N,sparsity", [
+    (40 * 128, 5 * 128, 8 * 512, 0.5),             # aligned everywhere
+    (40 * 128 + 40, 5 * 128 + 24, 8 * 512 - 8, 0.5),  # ragged M, K (last block column crosses K) and N tail
+    (72 * 128, 128, 7 * 512, 0.2),                 # one block per block-row: every tile is a single block
+    (64 * 128 + 8, 9 * 128, 4096, 0.85),           # very sparse: several block-rows stay empty
+])
+def test_bcsr_wide_tiles_parity(m, k, N, sparsity):
+    a = synth.block_sparse_bernoulli(m, k, 128, 128, sparsity, seed=31, dtype="bf16")
+    assert _plan_bn(a, N) == 512
+    B = synth.dense_normal(k, N, "bf16", seed=32)
+    C = gpu_spmm(a, "bcsr", 128, 128, B)
+    check_against_oracle(a, B, C)
+
+
+def test_bcsr_wide_tiles_empty_block_rows_and_rerun_bitwise():
+    rng = np.random.default_rng(5)
+    m, k, N = 48 * 128, 6 * 128, 4096
+    a = synth.block_sparse_bernoulli(m, k, 128, 128, 0.6, seed=33, dtype="bf16")
+    # empty out every fifth block-row
+    keep = np.ones(a.nnz, dtype=bool)
+    rows = np.repeat(np.arange(a.m), np.diff(a.row_ptr))
+    keep[(rows // 128) % 5 == 2] = False
+    rp = np.zeros(a.m + 1, dtype=np.int64)
+    np.add.at(rp, rows[keep] + 1, 1)
+    a2 = synth.Csr(a.m, a.k, np.cumsum(rp).astype(np.int32), a.col_idx[keep], a.values[keep], a.dtype)
+    assert _plan_bn(a2, N) == 512
+    B = synth.dense_normal(k, N, "bf16", seed=34)
+    C1 = gpu_spmm(a2, "bcsr", 128, 128, B)
+    C2 = gpu_spmm(a2, "bcsr", 128, 128, B)
+    assert np.array_equal(C1, C2)
+    assert not C1[2 * 128:3 * 128].any()  # an empty block-row: exact zeros
+    cols = np.sort(rng.choice(N, 256, replace=False))
+    check_against_oracle(a2, B, C1, cols)
+
+
+def test_bcsr_wide_tiles_times_identity_is_A_bit_exact():
+    m, k = 288 * 128, 512
+    a = synth.block_sparse_bernoulli(m, k, 128, 128, 0.3, seed=35, dtype="bf16")
+    N = 512
+    assert _plan_bn(a, N) == 512 and k == N
+    I = synth.dense_identity(k, "bf16")
+    C = gpu_spmm(a, "bcsr", 128, 128, I)
+    dense = np.zeros((m, k), dtype=np.uint16)
+    rows = np.repeat(np.arange(m), np.diff(a.row_ptr))
+    dense[rows, a.col_idx] = a.values
+    dense[dense == 0x8000] = 0  # a stored -0.0 times 1.0, added to the +0.0 the sum starts from, is +0.0
+    assert np.array_equal(C, dense)
+
 # ------------------------------------------------------------------ WCSR
 @pytest.mark.parametrize("b_row", [16, 32, 64])
 @pytest.mark.parametrize("m,k,N,density,task_cols", [

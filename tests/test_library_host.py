@@ -168,3 +168,12 @@ def test_plan_follows_tile_width_rule():
             assert p.workgroups == 2 * p.n_tiles
     finally:
         asp.asp_destroy(h)
+    # 128x128 blocks with at least one 512-wide tile per compute unit (256 assumed without a device): 512 joins the candidates
+    a = synth.block_sparse_bernoulli(2048, 256, 128, 128, 0.0, 2)
+    h = asp.asp_create_from_csr("bcsr", "bf16", 128, 128, a.m, a.k, a.row_ptr, a.col_idx, a.values, flags=HOST)
+    try:
+        for N, cands in ((16384, [64, 128, 256, 512]), (8192, [64, 128, 256, 512]), (4096, [64, 128, 256]), (8192 + 64, [64, 128, 256, 512])):
+            p = asp.asp_plan_spmm(h, N)
+            assert p.bn == oracle.choose_bn(N, cands), (N, p.bn)
+    finally:
+        asp.asp_destroy(h)
