@@ -110,9 +110,15 @@ __global__ __launch_bounds__(WM *WN * 64, (BR / WM) * (BN / WN) > 8192 ? 1 : 2) 
     const int wm = wave / WN, wn = wave % WN;
 
     // ---- this workgroup's tiles: every stride-th tile of its XCD's run ------------------------------
-    const int xcd = blockIdx.x & 7, stride = gridDim.x >> 3;
+    // (the position inside a round of `stride` tiles alternates direction from round to round: the run is
+    // sorted by weight, and dealt in the same direction every time the first workgroup would get the
+    // heaviest tile of every round)
+    const int xcd = blockIdx.x & 7, stride = gridDim.x >> 3, wg = blockIdx.x >> 3;
+    const int run_begin = __builtin_amdgcn_readfirstlane(runs.start[xcd]);
     const int run_end = __builtin_amdgcn_readfirstlane(runs.start[xcd + 1]);
-    int idx_cur = __builtin_amdgcn_readfirstlane(runs.start[xcd]) + (blockIdx.x >> 3);
+    auto tile_of_round = [&](int r) { return run_begin + r * stride + ((r & 1) ? stride - 1 - wg : wg); };
+    int round = 0;
+    int idx_cur = tile_of_round(0);
     if (idx_cur >= run_end) return;
 
     // ---- lane-invariant parts of the LDS read addresses ------------------------------------------
@@ -200,9 +206,9 @@ __global__ __launch_bounds__(WM *WN * 64, (BR / WM) * (BN / WN) > 8192 ? 1 : 2) 
     decode(idx_cur, cur_t, nxt_voff);
     cursor_enter(cur_t, nxt_voff);
     nxt_t = cur_t;
-    if (idx_cur + stride < run_end) {
+    if (tile_of_round(1) < run_end) {
         have_next = 1;
-        decode(idx_cur + stride, nxt_t, nxt_voff);
+        decode(tile_of_round(1), nxt_t, nxt_voff);
     }
 
     // request the cursor's slice into ring buffer buf and move the cursor on
@@ -364,7 +370,7 @@ __global__ __launch_bounds__(WM *WN * 64, (BR / WM) * (BN / WN) > 8192 ? 1 : 2) 
 
         // ---- tile boundary ------------------------------------------------------------------------
         // parameters of the tile after the next one: requested now, needed after the epilogue
-        const int idx_nn = idx_cur + 2 * stride;
+        const int idx_nn = tile_of_round(round + 2);
         Tile tnn = tc;
         uint32_t voff_nn[Cfg::B_LPW];
 #pragma unroll
@@ -430,7 +436,8 @@ __global__ __launch_bounds__(WM *WN * 64, (BR / WM) * (BN / WN) > 8192 ? 1 : 2) 
         }
 #endif
         if (!have_next) break;
-        idx_cur += stride;
+        ++round;
+        idx_cur = tile_of_round(round);
         cur_t = nxt_t;
         if (pf_in_next) pf_in_next = 0;          // the cursor's tile is now the current one
         else cursor_enter(nxt_t, nxt_voff);     // the cursor never left the finished tile: it follows

@@ -76,10 +76,18 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    // ---- this workgroup's tiles: every stride-th tile of its XCD's run ------------------------------
-    const int xcd = blockIdx.x & 7, stride = gridDim.x >> 3;
+    // ---- this workgroup's tiles: one of every `stride` consecutive tiles of its XCD's run.  The run is
+    // sorted by weight, so the position inside a round alternates direction from round to round:
+    // dealt in the same direction every time, the first workgroup would get the heaviest tile of every
+    // round and finish last. -------------------------------------------------------------------------
+    const int xcd = blockIdx.x & 7, stride = gridDim.x >> 3, wg = blockIdx.x >> 3;
+    const int run_begin = __builtin_amdgcn_readfirstlane(runs.start[xcd]);
     const int run_end = __builtin_amdgcn_readfirstlane(runs.start[xcd + 1]);
-    int idx_cur = __builtin_amdgcn_readfirstlane(runs.start[xcd]) + (blockIdx.x >> 3);
+    auto tile_of_round = [&](int r) __attribute__((always_inline)) {
+        return run_begin + r * stride + ((r & 1) ? stride - 1 - wg : wg);
+    };
+    int round = 0;
+    int idx_cur = tile_of_round(0);
     if (idx_cur >= run_end) return;
 
     // ---- LDS read addresses: one register per ring buffer, everything else is an immediate ----------
@@ -326,9 +334,9 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
         pf_bcol = bcol0;
         cursor_set_tile(colb);
         cursor_set_block();
-        if (idx_cur + stride < run_end) {
+        if (tile_of_round(1) < run_end) {
             have_next = 1;
-            decode(idx_cur + stride, n_br, n_n0, n_nb, n_blk0, n_bcol0, n_col);
+            decode(tile_of_round(1), n_br, n_n0, n_nb, n_blk0, n_bcol0, n_col);
         }
     }
 #pragma unroll
@@ -367,7 +375,7 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
         // ---- tile boundary ------------------------------------------------------------------------
         mfma_drain();
         // parameters of the tile after the next one: requested now, needed after the epilogue
-        const int idx_nn = idx_cur + 2 * stride;
+        const int idx_nn = tile_of_round(round + 2);
         int nn_br = 0, nn_n0 = 0, nn_nb = 0, nn_blk0 = 0, nn_bcol0 = 0;
         uint32_t nn_col = 0;
         if (idx_nn < run_end) decode(idx_nn, nn_br, nn_n0, nn_nb, nn_blk0, nn_bcol0, nn_col);
@@ -425,7 +433,8 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
         // reading its staging area first
         wait_vmcnt_and_lds<63>();
         barrier_no_fence();
-        idx_cur += stride;
+        ++round;
+        idx_cur = tile_of_round(round);
         c_br = n_br;
         c_n0 = n_n0;
         c_nb = n_nb;
