@@ -146,6 +146,41 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
     return res
 
 
+# The CDNA4 ladder (each rung = the library with benchmarking switches set; the switches only ever select
+# among kernels that are built and parity-tested) and the tile-width / tile-order sweeps, after the
+# paper's feature-by-feature study (Sections III-A..III-F, Table II) and its tile-width study (Section IV-C).
+ABLATION = [
+    ("MFMA, synchronous register-staged loads, one tile per workgroup, 128x256 tiles",
+     {"ASP_BCSR_KERNEL": "regstage", "ASP_BCSR_BN": "256"}),
+    ("+ direct-to-LDS ring, resident workgroups (2 per CU), static XCD-aware schedule, 128x256 tiles",
+     {"ASP_BCSR_BN": "256"}),
+    ("  same, 128x128 tiles", {"ASP_BCSR_BN": "128"}),
+    ("  same, 128x64 tiles", {"ASP_BCSR_BN": "64"}),
+    ("+ 128x128 wave tiles, one wave per SIMD, hand-ordered issue, 128x512 tiles (default)", {}),
+    ("  same, tiles dealt without regard to XCDs", {"ASP_BCSR_XCD_AWARE": "0"}),
+    ("  same, 1 N-tile per group", {"ASP_BCSR_GROUP_N": "1"}),
+    ("  same, 4 N-tiles per group", {"ASP_BCSR_GROUP_N": "4"}),
+]
+
+
+def run_ablation(args):
+    import subprocess
+    rows = []
+    for label, env in ABLATION:
+        e = dict(os.environ)
+        e.update(env)
+        cmd = [sys.executable, os.path.abspath(__file__), "--workload", args.workload, "--also", "", "--no-cpu-baseline",
+               "--steps", str(args.steps), "--warmup", str(args.warmup)]
+        out = subprocess.run(cmd, env=e, capture_output=True, text=True, timeout=600)
+        if out.returncode != 0:
+            rows.append({"variant": label, "switches": env, "error": out.stderr[-300:]})
+            continue
+        d = json.loads(out.stdout.strip().splitlines()[-1])
+        rows.append({"variant": label, "switches": env, "kernel_ms": d["roofline"]["kernel_ms_avg"],
+                     "achieved_tflops": d["roofline"]["achieved"], "frac": d["roofline"]["frac"], "bn": d["config"]["bn"]})
+    print(json.dumps({"ablation": rows, "workload": args.workload, "steps": args.steps}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -157,11 +192,17 @@ def main():
     ap.add_argument("--copy-reference", action="store_true",
                     help="only run a plain 1 GiB device copy (3 launches): the kernel of known size against "
                          "which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
+    ap.add_argument("--ablation", action="store_true",
+                    help="run the BCSR workload once per kernel variant (child processes) and print one JSON object")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (one MI355X, no collectives); run with --gpus 1",
               file=sys.stderr)
         sys.exit(2)
+
+    if args.ablation:
+        run_ablation(args)
+        return
 
     import torch
     from paper_2604_17834_amd import binding as asp

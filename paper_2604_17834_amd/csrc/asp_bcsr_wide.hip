@@ -68,7 +68,7 @@ template <bool KAL>
 __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     const int4 *__restrict__ rank_info, const int32_t *__restrict__ block_col_idx,
     const uint16_t *__restrict__ a_packed, const uint16_t *__restrict__ B, uint16_t *__restrict__ C, int M, int K,
-    int N, int n_rows, int n_blocks, int n_tiles, int group_n, XcdRuns runs) {
+    int N, int n_rows, int n_blocks, int n_tiles, int group_n, int xcd_aware, XcdRuns runs) {
     using Cfg = WideCfg;
     constexpr int NS = Cfg::NS, NW = Cfg::NW, KS = Cfg::KS, BR = Cfg::BR, BN = Cfg::BN, MT = Cfg::MT, NTL = Cfg::NTL;
     __shared__ __attribute__((aligned(1024))) uint8_t lds[Cfg::LDS_BYTES];
@@ -80,7 +80,10 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     // sorted by weight, so the position inside a round alternates direction from round to round:
     // dealt in the same direction every time, the first workgroup would get the heaviest tile of every
     // round and finish last. -------------------------------------------------------------------------
-    const int xcd = blockIdx.x & 7, stride = gridDim.x >> 3, wg = blockIdx.x >> 3;
+    // (xcd_aware = 0, a benchmarking switch: one run for all workgroups, i.e. neighbouring tiles land on
+    // different XCDs and share nothing in L2)
+    const int xcd = xcd_aware ? blockIdx.x & 7 : 0, stride = xcd_aware ? gridDim.x >> 3 : gridDim.x;
+    const int wg = xcd_aware ? blockIdx.x >> 3 : blockIdx.x;
     const int run_begin = __builtin_amdgcn_readfirstlane(runs.start[xcd]);
     const int run_end = __builtin_amdgcn_readfirstlane(runs.start[xcd + 1]);
     auto tile_of_round = [&](int r) __attribute__((always_inline)) {
@@ -494,16 +497,22 @@ bool bcsr_wide_launch(const asp_handle *h, const void *B, void *C, int64_t N, co
     int64_t workers = h->n_cus;  // one resident workgroup per CU: the ring takes the whole LDS
     if (workers > n_rows * p.n_tiles) workers = n_rows * p.n_tiles;
     workers = std::max<int64_t>(8, workers / 8 * 8);  // the same number of workgroups on every XCD
-    const XcdRuns runs = cut_runs(h->hb.sorted_weight_prefix, n_rows, p.n_tiles, group_n);
+    static const int env_xcd = [] {  // benchmarking switch only: 0 = ignore the XCDs when dealing tiles
+        const char *e = std::getenv("ASP_BCSR_XCD_AWARE");
+        return e ? std::atoi(e) : 1;
+    }();
+    XcdRuns runs = cut_runs(h->hb.sorted_weight_prefix, n_rows, p.n_tiles, group_n);
+    if (!env_xcd)
+        for (int x = 1; x <= 8; ++x) runs.start[x] = runs.start[8];
     dim3 grid((unsigned)workers), block(256);
     if (h->k % 128 == 0)
         hipLaunchKernelGGL(bcsr_spmm_wide_kernel<true>, grid, block, 0, stream, (const int4 *)h->d_rank_info,
                            h->d_col_idx, (const uint16_t *)h->d_values, (const uint16_t *)B, (uint16_t *)C, (int)h->m,
-                           (int)h->k, (int)N, (int)n_rows, (int)h->n_units, p.n_tiles, group_n, runs);
+                           (int)h->k, (int)N, (int)n_rows, (int)h->n_units, p.n_tiles, group_n, env_xcd, runs);
     else
         hipLaunchKernelGGL(bcsr_spmm_wide_kernel<false>, grid, block, 0, stream, (const int4 *)h->d_rank_info,
                            h->d_col_idx, (const uint16_t *)h->d_values, (const uint16_t *)B, (uint16_t *)C, (int)h->m,
-                           (int)h->k, (int)N, (int)n_rows, (int)h->n_units, p.n_tiles, group_n, runs);
+                           (int)h->k, (int)N, (int)n_rows, (int)h->n_units, p.n_tiles, group_n, env_xcd, runs);
     return true;
 }
 
