@@ -68,7 +68,7 @@ template <bool KAL>
 __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     const int4 *__restrict__ rank_info, const int32_t *__restrict__ block_col_idx,
     const uint16_t *__restrict__ a_packed, const uint16_t *__restrict__ B, uint16_t *__restrict__ C, int M, int K,
-    int N, int n_rows, int n_blocks, int n_tiles, int group_n, int xcd_aware, XcdRuns runs) {
+    int N, int n_rows, int n_brows, int n_blocks, int n_tiles, int group_n, int xcd_aware, XcdRuns runs) {
     using Cfg = WideCfg;
     constexpr int NS = Cfg::NS, NW = Cfg::NW, KS = Cfg::KS, BR = Cfg::BR, BN = Cfg::BN, MT = Cfg::MT, NTL = Cfg::NTL;
     __shared__ __attribute__((aligned(1024))) uint8_t lds[Cfg::LDS_BYTES];
@@ -89,9 +89,26 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     auto tile_of_round = [&](int r) __attribute__((always_inline)) {
         return run_begin + r * stride + ((r & 1) ? stride - 1 - wg : wg);
     };
+    // Rows of C of block-rows without stored blocks (ranks n_rows .. n_brows-1): every workgroup clears
+    // its share of each of them when its stream has ended (whole rows: one contiguous span, N % 8 == 0).
+    auto clear_empty_rows = [&]() __attribute__((always_inline)) {
+        const uint4 z = {0u, 0u, 0u, 0u};
+        for (int e = n_rows; e < n_brows; ++e) {
+            const int br = __builtin_amdgcn_readfirstlane(rank_info[e].x);
+            const int r0 = br * Cfg::BR, r1 = r0 + Cfg::BR < M ? r0 + Cfg::BR : M;
+            uint16_t *dst = C + (int64_t)r0 * N;
+            const int64_t n16 = (int64_t)(r1 - r0) * N / 8;
+            const int64_t per = (n16 + gridDim.x - 1) / gridDim.x;
+            const int64_t lo = per * blockIdx.x, hi = lo + per < n16 ? lo + per : n16;
+            for (int64_t i = lo + tid; i < hi; i += 256) store_c16(dst + i * 8, z);
+        }
+    };
     int round = 0;
     int idx_cur = tile_of_round(0);
-    if (idx_cur >= run_end) return;
+    if (idx_cur >= run_end) {
+        clear_empty_rows();
+        return;
+    }
 
     // ---- LDS read addresses: one register per ring buffer, everything else is an immediate ----------
     // A fragments: lane-linear 16 bytes.  B fragments, transposing read: lane i of a 16-lane group
@@ -457,6 +474,7 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     // the cursor's repeated requests at the end of the stream still write LDS: they must have landed
     // before the workgroup gives its LDS back
     wait_vmcnt_and_lds<0>();
+    clear_empty_rows();
 #undef ASP_FENCE
 #undef ASP_WIDE_STEP
 #undef ASP_MFMA
@@ -465,7 +483,8 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
 #undef ASP_B_BASE
 }
 
-// rows of C that belong to block-rows without stored blocks (ranks n_rows .. n_brows-1)
+// rows of C that belong to block-rows without stored blocks (ranks n_rows .. n_brows-1), for handles
+// that have no stored block at all
 __global__ __launch_bounds__(256) void bcsr_clear_empty_rows_kernel(const int4 *__restrict__ rank_info, int n_rows,
                                                                     uint16_t *__restrict__ C, int M, int N, int BR) {
     const int br = rank_info[n_rows + blockIdx.x].x;
@@ -488,7 +507,7 @@ bool bcsr_wide_launch(const asp_handle *h, const void *B, void *C, int64_t N, co
     int group_n = env_group > 0 ? env_group : 2;
     if (group_n > p.n_tiles) group_n = p.n_tiles;
     const int64_t n_rows = h->hb.n_nonempty, n_empty = h->n_brows - n_rows;
-    if (n_empty > 0) {
+    if (n_empty > 0 && n_rows == 0) {  // nothing to multiply: the clearing is all there is
         dim3 grid((unsigned)n_empty, 16), block(256);
         hipLaunchKernelGGL(bcsr_clear_empty_rows_kernel, grid, block, 0, stream, (const int4 *)h->d_rank_info, (int)n_rows,
                            (uint16_t *)C, (int)h->m, (int)N, 128);
@@ -508,11 +527,11 @@ bool bcsr_wide_launch(const asp_handle *h, const void *B, void *C, int64_t N, co
     if (h->k % 128 == 0)
         hipLaunchKernelGGL(bcsr_spmm_wide_kernel<true>, grid, block, 0, stream, (const int4 *)h->d_rank_info,
                            h->d_col_idx, (const uint16_t *)h->d_values, (const uint16_t *)B, (uint16_t *)C, (int)h->m,
-                           (int)h->k, (int)N, (int)n_rows, (int)h->n_units, p.n_tiles, group_n, env_xcd, runs);
+                           (int)h->k, (int)N, (int)n_rows, (int)h->n_brows, (int)h->n_units, p.n_tiles, group_n, env_xcd, runs);
     else
         hipLaunchKernelGGL(bcsr_spmm_wide_kernel<false>, grid, block, 0, stream, (const int4 *)h->d_rank_info,
                            h->d_col_idx, (const uint16_t *)h->d_values, (const uint16_t *)B, (uint16_t *)C, (int)h->m,
-                           (int)h->k, (int)N, (int)n_rows, (int)h->n_units, p.n_tiles, group_n, env_xcd, runs);
+                           (int)h->k, (int)N, (int)n_rows, (int)h->n_brows, (int)h->n_units, p.n_tiles, group_n, env_xcd, runs);
     return true;
 }
 
