@@ -160,7 +160,10 @@ __global__ __launch_bounds__(WM *WN * 64, (BR / WM) * (BN / WN) > 8192 ? 1 : 2) 
         const int grp = idx / per_group, in_grp = idx - grp * per_group;
         const int left = n_tiles - grp * group_n;
         const int gw = left < group_n ? left : group_n;  // the last group may be narrower
-        const int rank = in_grp / gw, nt = grp * group_n + (in_grp - rank * gw);
+        // heaviest block-row first in even groups, lightest first in odd ones: neighbours in the order,
+        // which run at the same time, then have similar weights across group boundaries too
+        const int pos = in_grp / gw, nt = grp * group_n + (in_grp - pos * gw);
+        const int rank = (grp & 1) ? n_brows - 1 - pos : pos;
         const int4 ri = rank_info[rank];
         // the index is the same for the whole workgroup: tell the compiler, so that everything derived
         // from a tile's parameters stays in scalar registers
@@ -477,12 +480,14 @@ XcdRuns cut_runs(const std::vector<int64_t> &pre, int64_t nbr, int n_tiles, int 
             continue;
         }
         const int64_t gw = std::min<int64_t>(group_n, n_tiles - g * group_n);
-        // first rank whose prefix (times the group width) reaches the remainder
+        // first position whose prefix (times the group width) reaches the remainder; odd groups walk
+        // the block-rows lightest first
         const int64_t rem = target - acc;
+        auto prefix = [&](int64_t j) { return (g & 1) ? rows_weight - pre[nbr - j] : pre[j]; };
         int64_t lo = 0, hi = nbr;
         while (lo < hi) {
             int64_t mid = (lo + hi) / 2;
-            if (pre[mid] * gw < rem) lo = mid + 1; else hi = mid;
+            if (prefix(mid) * gw < rem) lo = mid + 1; else hi = mid;
         }
         r.start[x] = (int)(g * group_n * nbr + lo * gw);
     }

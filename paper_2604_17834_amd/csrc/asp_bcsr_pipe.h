@@ -62,8 +62,8 @@ struct XcdRuns {
     int start[9];
 };
 
-// Cut the tile order (groups of group_n N-tiles, inside a group the n_rows heaviest block-rows in
-// order, each repeated over the group's N-tiles) into 8 runs of equal weight; pre[] are the prefix
+// Cut the tile order (groups of group_n N-tiles, inside a group the n_rows heaviest block-rows,
+// heaviest first in even groups and lightest first in odd ones, each repeated over the group's N-tiles) into 8 runs of equal weight; pre[] are the prefix
 // sums of the block-rows' tile weights in that order.
 XcdRuns cut_runs(const std::vector<int64_t> &pre, int64_t n_rows, int n_tiles, int group_n);
 

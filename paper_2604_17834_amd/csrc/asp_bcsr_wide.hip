@@ -148,7 +148,10 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
         const int grp = idx / per_group, in_grp = idx - grp * per_group;
         const int left = n_tiles - grp * group_n;
         const int gw = left < group_n ? left : group_n;  // the last group may be narrower
-        const int rank = in_grp / gw, nt = grp * group_n + (in_grp - rank * gw);
+        // heaviest block-row first in even groups, lightest first in odd ones: neighbours in the order,
+        // which run at the same time, then have similar weights across group boundaries too
+        const int pos = in_grp / gw, nt = grp * group_n + (in_grp - pos * gw);
+        const int rank = (grp & 1) ? n_rows - 1 - pos : pos;
         const int4 ri = rank_info[rank];
         br = __builtin_amdgcn_readfirstlane(ri.x);
         blk0 = __builtin_amdgcn_readfirstlane(ri.y);
