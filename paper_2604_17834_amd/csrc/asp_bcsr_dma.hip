@@ -110,13 +110,12 @@ __global__ __launch_bounds__(WM *WN * 64, (BR / WM) * (BN / WN) > 8192 ? 1 : 2) 
     const int wm = wave / WN, wn = wave % WN;
 
     // ---- this workgroup's tiles: every stride-th tile of its XCD's run ------------------------------
-    // (the position inside a round of `stride` tiles alternates direction from round to round: the run is
-    // sorted by weight, and dealt in the same direction every time the first workgroup would get the
-    // heaviest tile of every round)
+    // (the order of block-rows was built so that this deals every workgroup one weight-balanced list per
+    // group of N-tiles)
     const int xcd = blockIdx.x & 7, stride = gridDim.x >> 3, wg = blockIdx.x >> 3;
     const int run_begin = __builtin_amdgcn_readfirstlane(runs.start[xcd]);
     const int run_end = __builtin_amdgcn_readfirstlane(runs.start[xcd + 1]);
-    auto tile_of_round = [&](int r) { return run_begin + r * stride + ((r & 1) ? stride - 1 - wg : wg); };
+    auto tile_of_round = [&](int r) { return run_begin + r * stride + wg; };
     int round = 0;
     int idx_cur = tile_of_round(0);
     if (idx_cur >= run_end) return;

@@ -76,10 +76,9 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    // ---- this workgroup's tiles: one of every `stride` consecutive tiles of its XCD's run.  The run is
-    // sorted by weight, so the position inside a round alternates direction from round to round:
-    // dealt in the same direction every time, the first workgroup would get the heaviest tile of every
-    // round and finish last. -------------------------------------------------------------------------
+    // ---- this workgroup's tiles: every stride-th tile of its XCD's run.  The order of block-rows was
+    // built (per handle) so that this deals every workgroup one weight-balanced list per group of
+    // N-tiles. -----------------------------------------------------------------------------------------
     // (xcd_aware = 0, a benchmarking switch: one run for all workgroups, i.e. neighbouring tiles land on
     // different XCDs and share nothing in L2)
     const int xcd = xcd_aware ? blockIdx.x & 7 : 0, stride = xcd_aware ? gridDim.x >> 3 : gridDim.x;
@@ -87,7 +86,7 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     const int run_begin = __builtin_amdgcn_readfirstlane(runs.start[xcd]);
     const int run_end = __builtin_amdgcn_readfirstlane(runs.start[xcd + 1]);
     auto tile_of_round = [&](int r) __attribute__((always_inline)) {
-        return run_begin + r * stride + ((r & 1) ? stride - 1 - wg : wg);
+        return run_begin + r * stride + wg;
     };
     // Rows of C of block-rows without stored blocks (ranks n_rows .. n_brows-1): every workgroup clears
     // its share of each of them when its stream has ended (whole rows: one contiguous span, N % 8 == 0).

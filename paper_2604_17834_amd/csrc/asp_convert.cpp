@@ -137,13 +137,43 @@ void csr_to_bcsr(int64_t m, int64_t k, const int32_t *row_ptr, const int32_t *co
 // heaviest first (ties: lower block-row first), with prefix sums of the tile weights in that order.
 void bcsr_build_schedule(HostBcsr &b) {
     const int64_t nbr = (int64_t)b.block_row_ptr.size() - 1;
-    std::vector<int32_t> order(nbr);
-    for (int64_t i = 0; i < nbr; ++i) order[i] = (int32_t)i;
+    std::vector<int32_t> sorted(nbr);
+    for (int64_t i = 0; i < nbr; ++i) sorted[i] = (int32_t)i;
     auto len = [&](int32_t r) { return b.block_row_ptr[r + 1] - b.block_row_ptr[r]; };
-    std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return len(x) > len(y); });
+    std::stable_sort(sorted.begin(), sorted.end(), [&](int32_t x, int32_t y) { return len(x) > len(y); });
+    int64_t n_nonempty = 0;
+    while (n_nonempty < nbr && len(sorted[n_nonempty]) > 0) ++n_nonempty;
+
+    // The kernels deal consecutive entries of this order to the workgroups of an XCD round-robin, LISTS
+    // block-rows per round (each block-row repeated over the N-tiles of a group).  So entry j belongs to
+    // list j % LISTS, and a workgroup walks one list per group of N-tiles.  The non-empty block-rows are
+    // spread over the lists by the longest-processing-time rule (heaviest first, each to the list that is
+    // lightest so far; weight = stored blocks + 1 for the tile's epilogue), which keeps the lists' sums
+    // within one block-row of each other; list entries keep the descending order, so the entries of one
+    // round -- which run at the same time -- still have similar weights.  Empty block-rows follow.
+    constexpr int LISTS = 16;
+    std::vector<std::vector<int32_t>> lists(LISTS);
+    std::vector<int64_t> load(LISTS, 0);
+    for (int64_t r = 0; r < n_nonempty; ++r) {
+        // among the lists with the fewest entries (the round being filled), the lightest one
+        int best = -1;
+        size_t fewest = lists[0].size();
+        for (int l = 1; l < LISTS; ++l) fewest = std::min(fewest, lists[l].size());
+        for (int l = 0; l < LISTS; ++l)
+            if (lists[l].size() == fewest && (best < 0 || load[l] < load[best])) best = l;
+        lists[best].push_back(sorted[r]);
+        load[best] += len(sorted[r]) + 1;
+    }
+    std::vector<int32_t> order;
+    order.reserve(nbr);
+    for (size_t e = 0; order.size() < (size_t)n_nonempty; ++e)
+        for (int l = 0; l < LISTS; ++l)
+            if (e < lists[l].size()) order.push_back(lists[l][e]);
+    for (int64_t r = n_nonempty; r < nbr; ++r) order.push_back(sorted[r]);
+
     b.rank_info.resize((size_t)nbr * 4);
     b.sorted_weight_prefix.assign(nbr + 1, 0);
-    b.n_nonempty = 0;
+    b.n_nonempty = n_nonempty;
     for (int64_t r = 0; r < nbr; ++r) {
         const int32_t br = order[r];
         b.rank_info[4 * r + 0] = br;
@@ -151,7 +181,6 @@ void bcsr_build_schedule(HostBcsr &b) {
         b.rank_info[4 * r + 2] = len(br);
         b.rank_info[4 * r + 3] = len(br) > 0 ? b.block_col_idx[b.block_row_ptr[br]] : 0;  // column of its first block
         b.sorted_weight_prefix[r + 1] = b.sorted_weight_prefix[r] + len(br) + 1;
-        if (len(br) > 0) b.n_nonempty = r + 1;
     }
 }
 
