@@ -47,9 +47,12 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
     import numpy as np
 
     t0 = time.time()
-    a, fmt, b_row, b_col, N, dt, seedB = synth.workload(name)
-    B = synth.dense_normal(a.k, N, dt, seedB)
+    # "<workload>_xt": the same matrix through the K-contiguous entry, Y[N x m] = X[N x k] x A^T
+    xt = name.endswith("_xt")
+    a, fmt, b_row, b_col, N, dt, seedB = synth.workload(name[:-3] if xt else name)
+    B = synth.dense_normal(N, a.k, dt, seedB) if xt else synth.dense_normal(a.k, N, dt, seedB)
     t_gen = time.time() - t0
+    spmm = asp.asp_spmm_xt if xt else asp.asp_spmm
 
     stream = torch.cuda.current_stream().cuda_stream
     t0 = time.time()
@@ -60,14 +63,14 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
 
     if dt == "bf16":
         Bd = torch.from_numpy(B.view(np.int16)).cuda()
-        Cd = torch.empty((a.m, N), dtype=torch.int16, device="cuda")
+        Cd = torch.empty((N, a.m) if xt else (a.m, N), dtype=torch.int16, device="cuda")
     else:
         Bd = torch.from_numpy(B).cuda()
         Cd = torch.empty((a.m, N), dtype=torch.float32, device="cuda")
     bp, cp = Bd.data_ptr(), Cd.data_ptr()
 
     for _ in range(warmup):
-        asp.asp_spmm(h, bp, cp, N, stream)
+        spmm(h, bp, cp, N, stream)
     torch.cuda.synchronize()
     starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
     ends = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
@@ -75,7 +78,7 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
     w0 = time.perf_counter()
     for i in range(steps):
         starts[i].record()
-        asp.asp_spmm(h, bp, cp, N, stream)
+        spmm(h, bp, cp, N, stream)
         ends[i].record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - w0) * 1e3 / steps
@@ -123,16 +126,17 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
         # bounded sample: the oracle on a slice of B's columns (column j of C needs column j of B only)
         probe = min(N, 16)
         t0 = time.perf_counter()
-        oracle.spmm(a.m, a.k, a.row_ptr, a.col_idx, a.values, dt, np.ascontiguousarray(B[:, :probe]))
+        Bo = np.ascontiguousarray(B.T) if xt else B  # the oracle's operand is k x N
+        oracle.spmm(a.m, a.k, a.row_ptr, a.col_idx, a.values, dt, np.ascontiguousarray(Bo[:, :probe]))
         tp = time.perf_counter() - t0
         ncols = int(max(probe, min(N, 15.0 / max(tp / probe, 1e-9))))
         ncols = max(16, ncols // 16 * 16) if N >= 16 else N
-        Bs = np.ascontiguousarray(B[:, :ncols])
+        Bs = np.ascontiguousarray(Bo[:, :ncols])
         t0 = time.perf_counter()
         ref, S = oracle.spmm(a.m, a.k, a.row_ptr, a.col_idx, a.values, dt, Bs)
         tc = time.perf_counter() - t0
-        got = Cd[:, :ncols].cpu().numpy()
-        got = synth.to_f64(got.view(np.uint16), "bf16") if dt == "bf16" else got.astype(np.float64)
+        got = Cd[:ncols].cpu().numpy().T if xt else Cd[:, :ncols].cpu().numpy()
+        got = synth.to_f64(np.ascontiguousarray(got).view(np.uint16), "bf16") if dt == "bf16" else got.astype(np.float64)
         bound = 1e-2 * S + 1e-5 if dt == "bf16" else 1e-5 * S
         ok = bool(np.isfinite(got).all() and (np.abs(got - ref) <= bound).all())
         res["cpu_baseline"] = {"value": 2.0 * a.nnz * ncols / tc / 1e9, "unit": "GFLOP/s", "cores": oracle.num_threads(),

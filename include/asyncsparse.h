@@ -117,6 +117,18 @@ asp_status_t asp_create_from_csr(const asp_config_t *cfg, int64_t m, int64_t k, 
  */
 asp_status_t asp_spmm(const asp_handle_t *h, const void *B, void *C, int64_t N, void *stream);
 
+/*
+ * Y = X x A^T with K-contiguous dense operands: the same product as asp_spmm with B = X^T and C = Y^T, in
+ * the layout of the paper's LLM case study (Section IV-D: C = W X^T, activations stored tokens x hidden),
+ * so that projections can be chained without transposes.
+ * X: DEVICE, N x k row-major (leading dimension k).  Y: DEVICE, N x m row-major (leading dimension m), fully
+ * overwritten; Y must not alias X.  N >= 1.  BCSR handles (bf16) only; others return ASP_ERR_UNSUPPORTED.
+ * Asynchronous, never synchronises, never allocates.  fp32 accumulation, round-to-nearest-even to bf16;
+ * bitwise reproducible.  128x128 blocks with k % 8 == 0, m % 8 == 0, 16-byte aligned X and Y and at least
+ * one 128 x 512 tile per compute unit run on the matrix cores; everything else takes a slow generic kernel.
+ */
+asp_status_t asp_spmm_xt(const asp_handle_t *h, const void *X, void *Y, int64_t N, void *stream);
+
 /* host only: describe the handle */
 asp_status_t asp_get_info(const asp_handle_t *h, asp_info_t *info);
 

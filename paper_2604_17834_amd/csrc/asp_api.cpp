@@ -159,6 +159,15 @@ asp_status_t asp_spmm(const asp_handle_t *h, const void *B, void *C, int64_t N, 
     return wcsr_spmm_launch(h, B, C, N, (hipStream_t)stream);
 }
 
+asp_status_t asp_spmm_xt(const asp_handle_t *h, const void *X, void *Y, int64_t N, void *stream) {
+    if (!h || !X || !Y) return fail(ASP_ERR_INVALID_ARG, "null handle, X or Y");
+    if (N < 1) return fail(ASP_ERR_INVALID_ARG, "N must be >= 1");
+    if (h->device < 0) return fail(ASP_ERR_UNSUPPORTED, "handle was converted on the host only; it has no device arrays");
+    if (h->format != ASP_FMT_BCSR) return fail(ASP_ERR_UNSUPPORTED, "the K-contiguous entry is built for BCSR handles only");
+    if (N >= (1ll << 31) || h->m * N >= (1ll << 40) || h->k * N >= (1ll << 40)) return fail(ASP_ERR_UNSUPPORTED, "N too large");
+    return bcsr_spmm_xt_launch(h, X, Y, N, (hipStream_t)stream);
+}
+
 asp_status_t asp_get_info(const asp_handle_t *h, asp_info_t *info) {
     if (!h || !info) return fail(ASP_ERR_INVALID_ARG, "null handle or info");
     info->m = h->m;

@@ -33,6 +33,7 @@
 // free buffers, never read), so every step issues the same loads and the wait counts are constants.
 // Scheduling, swizzling, store accounting: as in the 64 x 128 kernel.
 #include <cstdlib>
+#include <cstring>
 
 #include "asp_bcsr_pipe.h"
 
@@ -53,7 +54,7 @@ struct WideCfg {
     static constexpr int NSTORE = MT * (32 / RPI);
     static constexpr int LDS_BYTES = NS * STAGE;
     static_assert(SPB == NS, "the ring is walked in step with the slices of a block");
-    static_assert(A_LPW == 2 && B_LPW == 8 && MT == 4 && NTL == 4, "the step below is written out for these");
+    static_assert(A_LPW == 2 && B_LPW == 8 && MT == 4 && NTL == 4 && TN == 128 && BR == 128, "the step below is written out for these");
     static_assert(NW * C_WAVE <= STAGE, "epilogue staging must fit into one ring buffer");
     static_assert(NSTORE + LPW + LPW / 2 < 64 && LPW % 2 == 0, "vmcnt is a 6-bit counter");
     static_assert(LDS_BYTES <= 163840, "LDS of one compute unit");
@@ -61,10 +62,20 @@ struct WideCfg {
 
 }  // namespace
 
-// rank_info[r] = {block-row, first stored block, number of stored blocks, block column of the first one} of the r-th heaviest
-// block-row; only the first n_rows (non-empty) ones are walked.  KAL: K is a multiple of the block
-// size, so no slice of B reaches past row K.
-template <bool KAL>
+// rank_info[r] = {block-row, first stored block, number of stored blocks, block column of the first one} of the r-th
+// block-row of the schedule; only the first n_rows (non-empty) ones are walked.  KAL: K is a multiple of the
+// block size, so no slice of the dense operand reaches past K.
+//
+// XT = false: C[M x N] = A x B, B is K x N row-major (paper, Section II-C).
+// XT = true:  Y[N x M] = X x A^T, X is N x K row-major -- the same product with both dense matrices
+//   transposed, i.e. K-contiguous activations in and out (the layout of the paper's LLM case study,
+//   Section IV-D: C = W X^T with X stored tokens x hidden).  In the argument list B is then X and C is Y; a
+//   tile is still (block-row, 512 columns of the product) = 128 outputs x 512 tokens.  What changes: a slice
+//   of X is 512 tokens x 64 bytes, laid out in LDS token-major (1 KB region = 16 tokens, the 16-byte chunk of
+//   a token XOR-swizzled by (token / 4) % 4) and read with plain 16-byte reads (it already is k-contiguous);
+//   the MFMA operands are not swapped, so a lane ends with 4 adjacent outputs of one token; the epilogue
+//   transposes 32 tokens x 128 outputs at a time and stores 256-byte row segments of Y.
+template <bool KAL, bool XT>
 __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     const int4 *__restrict__ rank_info, const int32_t *__restrict__ block_col_idx,
     const uint16_t *__restrict__ a_packed, const uint16_t *__restrict__ B, uint16_t *__restrict__ C, int M, int K,
@@ -90,16 +101,25 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     };
     // Rows of C of block-rows without stored blocks (ranks n_rows .. n_brows-1): every workgroup clears
     // its share of each of them when its stream has ended (whole rows: one contiguous span, N % 8 == 0).
+    // (XT: the block-row's outputs are up to 256 bytes in every row of Y)
     auto clear_empty_rows = [&]() __attribute__((always_inline)) {
         const uint4 z = {0u, 0u, 0u, 0u};
         for (int e = n_rows; e < n_brows; ++e) {
             const int br = __builtin_amdgcn_readfirstlane(rank_info[e].x);
             const int r0 = br * Cfg::BR, r1 = r0 + Cfg::BR < M ? r0 + Cfg::BR : M;
-            uint16_t *dst = C + (int64_t)r0 * N;
-            const int64_t n16 = (int64_t)(r1 - r0) * N / 8;
-            const int64_t per = (n16 + gridDim.x - 1) / gridDim.x;
-            const int64_t lo = per * blockIdx.x, hi = lo + per < n16 ? lo + per : n16;
-            for (int64_t i = lo + tid; i < hi; i += 256) store_c16(dst + i * 8, z);
+            if (!XT) {
+                uint16_t *dst = C + (int64_t)r0 * N;
+                const int64_t n16 = (int64_t)(r1 - r0) * N / 8;
+                const int64_t per = (n16 + gridDim.x - 1) / gridDim.x;
+                const int64_t lo = per * blockIdx.x, hi = lo + per < n16 ? lo + per : n16;
+                for (int64_t i = lo + tid; i < hi; i += 256) store_c16(dst + i * 8, z);
+            } else {
+                const int cpr = (r1 - r0) / 8;  // 16-byte units per row (M % 8 == 0)
+                const int64_t per = ((int64_t)N + gridDim.x - 1) / gridDim.x;
+                const int64_t lo = per * blockIdx.x, hi = lo + per < N ? lo + per : N;
+                for (int64_t t = lo + (tid >> 4); t < hi; t += 16)
+                    if ((tid & 15) < cpr) store_c16(C + t * M + r0 + (tid & 15) * 8, z);
+            }
         }
     };
     int round = 0;
@@ -117,24 +137,37 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     const int c_lane = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);  // chunk inside the 32-column tile
     const int sub = 8 * (lane & 1);                                // byte inside the chunk
     const uint32_t lds0 = lds_offset(lds);
-    uint32_t a_addr[NS], b_addr[NS][NTL];
+    // XT: lane l reads token wave*128 + j*32 + l%32, chunk 2*kk + l/32 of its 64 bytes; the swizzle makes
+    // the two k halves differ by more than an immediate, hence a second set of addresses (b_addr1).
+    uint32_t a_addr[NS], b_addr[NS][NTL], b_addr1[XT ? NS : 1][NTL];
 #pragma unroll
     for (int b = 0; b < NS; ++b) {
         a_addr[b] = lds0 + b * Cfg::STAGE + lane * 16;
 #pragma unroll
         for (int j = 0; j < NTL; ++j) {
-            const int c = (wave * Cfg::TN + j * 32) / 8 + c_lane;
-            b_addr[b][j] = lds0 + b * Cfg::STAGE + Cfg::A_STAGE + krow_lane * Cfg::B_ROW + ((c ^ sw) * 16) + sub;
+            if (!XT) {
+                const int c = (wave * Cfg::TN + j * 32) / 8 + c_lane;
+                b_addr[b][j] = lds0 + b * Cfg::STAGE + Cfg::A_STAGE + krow_lane * Cfg::B_ROW + ((c ^ sw) * 16) + sub;
+            } else {
+                const int t = wave * Cfg::TN + j * 32 + (lane & 31), f = (t >> 2) & 3, kg = lane >> 5;
+                const uint32_t tok = lds0 + b * Cfg::STAGE + Cfg::A_STAGE + (t >> 4) * 1024 + (t & 15) * 64;
+                b_addr[b][j] = tok + ((kg ^ f) * 16);
+                b_addr1[b][j] = tok + (((2 + kg) ^ f) * 16);
+            }
         }
         // opaque to the optimiser: otherwise it folds the buffer offset back into per-use additions
         asm volatile("" : "+v"(a_addr[b]), "+v"(b_addr[b][0]), "+v"(b_addr[b][1]), "+v"(b_addr[b][2]), "+v"(b_addr[b][3]));
+        if (XT) asm volatile("" : "+v"(b_addr1[b][0]), "+v"(b_addr1[b][1]), "+v"(b_addr1[b][2]), "+v"(b_addr1[b][3]));
     }
     // B source: a 1 KB region is one whole row of the slice; the i-th load of this wave fills row
     // i*NW + wave, whose swizzle (row & 3) is the wave number for every i: lane l fetches chunk
     // l ^ (wave << 2) so that it lands at position l.
+    // XT: a 1 KB region is 16 tokens x 64 bytes; the i-th load of this wave fills tokens 64*i + 16*wave
+    // + l/4, and lane l fetches chunk (l % 4) ^ ((l / 16) % 4) of its token so that it lands swizzled.
     const int b_chunk = lane ^ (wave << 2);
+    const int xt_chunk = (lane & 3) ^ ((lane >> 4) & 3), xt_token = 16 * wave + (lane >> 2);
     const uint32_t a_voff0 = (uint32_t)(wave * 1024 + lane * 16), a_voff1 = a_voff0 + NW * 1024;
-    const int64_t row_bytes = (int64_t)N * 2;
+    const int64_t row_bytes = XT ? (int64_t)K * 2 : (int64_t)N * 2;  // row of the dense input operand
     const uint32_t m0_base = __builtin_amdgcn_readfirstlane((int)(lds0 + wave * 1024));
 
     // ---- tile parameters, in named scalars: arrays or structs indexed at run time would be placed in
@@ -159,7 +192,7 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
         n0 = nt * BN;
         int col = n0 + 8 * b_chunk;
         col = col < N ? col : N - 8;  // chunks past N only feed columns that are never stored
-        colb = (uint32_t)col * 2;
+        colb = XT ? (uint32_t)n0 : (uint32_t)col * 2;
     };
 
     // ---- the request cursor: block pf_b (of pf_nb) of its tile, stored block pf_blk; the slice to
@@ -171,16 +204,35 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     uint32_t pf_voff[Cfg::B_LPW];     // per-lane byte offsets of the 8 rows this wave loads of a slice of B
     const uint8_t *pf_abase = nullptr; // next A slice to request
     const uint8_t *pf_bbase = nullptr; // first row of B of the next slice to request
+    int pf_n0 = 0;                      // XT: first token of the cursor's tile
+    const uint8_t *pf_xrow0 = nullptr;  // XT: X at (that token, k = 0)
     auto cursor_set_tile = [&](uint32_t colb) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < Cfg::B_LPW; ++i) pf_voff[i] = colb + (uint32_t)(i * NW + wave) * (uint32_t)row_bytes;
+        for (int i = 0; i < Cfg::B_LPW; ++i) {
+            if (!XT) {
+                pf_voff[i] = colb + (uint32_t)(i * NW + wave) * (uint32_t)row_bytes;
+            } else {
+                // tokens past N only feed columns of the product that are never stored: read the last one
+                int t = 64 * i + xt_token;
+                const int last = N - 1 - (int)colb;
+                t = t < last ? t : last;
+                // (not KAL: the k part is added per request, clamped to the row, from the row's start)
+                pf_voff[i] = (uint32_t)t * (uint32_t)row_bytes + (KAL ? xt_chunk * 16 : 0);
+            }
+        }
+        if (XT) {
+            pf_n0 = __builtin_amdgcn_readfirstlane((int)colb);
+            pf_xrow0 = (const uint8_t *)uniform_ptr((const uint8_t *)B + (int64_t)pf_n0 * row_bytes);
+        }
     };
     auto cursor_set_block = [&]() __attribute__((always_inline)) {
         // (made scalar here, well before the requests read them: a memory instruction may read a scalar
         // register only five wait states after a vector instruction wrote it, the compiler keeps such
         // wave-uniform values in vector registers at times, and it does not see the loads inside the asm)
         pf_abase = (const uint8_t *)uniform_ptr((const uint8_t *)a_packed + (int64_t)pf_blk * (BR * BR * 2));
-        pf_bbase = (const uint8_t *)uniform_ptr((const uint8_t *)B + (int64_t)pf_bcol * BR * row_bytes);
+        pf_bbase = (const uint8_t *)uniform_ptr(
+            XT ? (const uint8_t *)B + (int64_t)pf_n0 * row_bytes + (int64_t)pf_bcol * BR * 2
+               : (const uint8_t *)B + (int64_t)pf_bcol * BR * row_bytes);
         int nb_ = pf_blk + 1;
         nb_ = nb_ < n_blocks ? nb_ : n_blocks - 1;
         pf_bcol_ld = __builtin_amdgcn_readfirstlane(block_col_idx[nb_]);
@@ -217,6 +269,10 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
         for (int i = 0; i < MT; ++i) f.a[i] = *(const lds_bf16x8 *)(uintptr_t)(a_addr[buf] + (kk * MT + i) * 1024);
     };
     auto load_b = [&](int buf, int kk, Frags &f, int j) __attribute__((always_inline)) {
+        if (XT) {
+            f.b[j] = *(const lds_bf16x8 *)(uintptr_t)(kk ? b_addr1[buf][j] : b_addr[buf][j]);
+            return;
+        }
         const uint32_t p0 = b_addr[buf][j] + kk * 16 * Cfg::B_ROW;
         short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4v *)(uintptr_t)(p0));
         short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4v *)(uintptr_t)(p0 + 4 * Cfg::B_ROW));
@@ -231,15 +287,18 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     // The compiler does not see MFMAs here, so the wait states between the last MFMA of a tile and the
     // first read of its result are provided by hand (mfma_drain).
     f32x16 acc[MT][NTL];
+    // (XT: not swapped, D[m][n]: a lane ends with 4 adjacent outputs of one token)
+#define ASP_OP1(f, q) (XT ? f.a[(q) / NTL] : f.b[(q) % NTL])
+#define ASP_OP2(f, q) (XT ? f.b[(q) % NTL] : f.a[(q) / NTL])
 #define ASP_MFMA(f, q) \
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc[(q) / NTL][(q) % NTL]) : "v"(f.b[(q) % NTL]), "v"(f.a[(q) / NTL]))
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc[(q) / NTL][(q) % NTL]) : "v"(ASP_OP1(f, q)), "v"(ASP_OP2(f, q)))
     // the same with a direct-to-LDS load behind it: M0 = LDS destination of the wave's 1 KB region, then
     // the MFMA (the wait state the load needs after the write of M0), then the load of 16 bytes per lane
     // from sbase + voff
 #define ASP_MFMA_DMA(f, q, region_off, voff, sbase)                                                              \
     asm volatile("s_add_u32 m0, %3, %4\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\tglobal_load_lds_dwordx4 %5, %6" \
                  : "+a"(acc[(q) / NTL][(q) % NTL])                                                               \
-                 : "v"(f.b[(q) % NTL]), "v"(f.a[(q) / NTL]), "s"(m0_base), "i"(region_off), "v"(voff),          \
+                 : "v"(ASP_OP1(f, q)), "v"(ASP_OP2(f, q)), "s"(m0_base), "i"(region_off), "v"(voff),          \
                    "s"(uniform_ptr(sbase))                                                                       \
                  : "memory", "scc")
     // acc[i][j] = 0 x 0 + 0: clears a finished tile's accumulators on the matrix core, which is idle
@@ -255,9 +314,21 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
 
     // B row i*NW + wave of the slice at pf_bbase.  Not KAL: rows past K are read from row K-1 (they meet
     // the zero padding of A's last block column); s = slice inside the block.
-#define ASP_B_VOFF(s, i) \
-    (KAL ? pf_voff[i] : pf_voff[0] + (uint32_t)((((s) * KS + (i) * NW + wave) < K - pf_bcol * BR ? ((s) * KS + (i) * NW) : K - 1 - pf_bcol * BR - wave)) * (uint32_t)row_bytes)
-#define ASP_B_BASE(s) (KAL ? pf_bbase : pf_bbase - (int64_t)(s) * KS * row_bytes)
+    // XT, not KAL: 16-byte chunks past K are read from the last chunk of the row instead (K % 8 == 0).
+    // The offset counts from the start of the token's row (base pf_xrow0), so it never goes negative.
+    auto xt_voff_edge = [&](int s_, int i) __attribute__((always_inline)) {
+        int kc = pf_bcol * BR + s_ * KS + 8 * xt_chunk;
+        kc = kc < K - 8 ? kc : K - 8;
+        return pf_voff[i] + (uint32_t)kc * 2;
+    };
+#define ASP_B_VOFF(s, i)                                                                                        \
+    (XT ? (KAL ? pf_voff[i] : xt_voff_edge(s, i))                                                              \
+        : (KAL ? pf_voff[i]                                                                                     \
+               : pf_voff[0] + (uint32_t)((((s) * KS + (i) * NW + wave) < K - pf_bcol * BR ? ((s) * KS + (i) * NW) \
+                                                                                           : K - 1 - pf_bcol * BR - wave)) * \
+                                  (uint32_t)row_bytes))
+#define ASP_B_BASE(s) (XT ? (KAL ? pf_bbase : pf_xrow0) : (KAL ? pf_bbase : pf_bbase - (int64_t)(s) * KS * row_bytes))
+    const int64_t slice_step = XT ? (int64_t)KS * 2 : (int64_t)KS * row_bytes;  // next slice of the dense operand
 
     // ---- one step: slice S of a block, in ring buffer S.  The instruction order is fixed by hand
     // (nothing moves across a fence).  HI: the previous tile's stores may still be outstanding. ---------
@@ -341,7 +412,7 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
         ASP_FENCE();                                                                                               \
         ASP_PHASE(f1, f0, nb_, 0, ASP_RQ_B3, ASP_RQ_B4, ASP_RQ_B5, ASP_RQ_B6, ASP_RQ_B7, (void)0);                 \
         pf_abase = (const uint8_t *)uniform_ptr(pf_abase + Cfg::A_STAGE);                                          \
-        pf_bbase = (const uint8_t *)uniform_ptr(pf_bbase + KS * row_bytes);                                        \
+        pf_bbase = (const uint8_t *)uniform_ptr(pf_bbase + slice_step);                                            \
         if (HI_POSSIBLE) vm_hi = vm_hi > 0 ? vm_hi - 1 : 0;                                                        \
         ASP_FENCE();                                                                                               \
     } while (0)
@@ -376,7 +447,7 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
         for (int i = 0; i < Cfg::B_LPW; ++i)
             dma16_to_lds(ASP_B_BASE(s), ASP_B_VOFF(s, i), m0_base + s * Cfg::STAGE + Cfg::A_STAGE + i * NW * 1024);
         pf_abase += Cfg::A_STAGE;
-        pf_bbase += KS * row_bytes;
+        pf_bbase += slice_step;
     }
     wait_vmcnt_and_lds<2 * Cfg::LPW>();
     barrier_no_fence();
@@ -406,37 +477,42 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
         // until the next barrier
         const bool interior = c_br * BR + BR <= M && c_n0 + BN <= N;
         uint8_t *sc = lds + (NS - 1) * Cfg::STAGE + wave * Cfg::C_WAVE;
-        const int grow0 = c_br * BR + lane / Cfg::CPR;
-        const int gcol0 = c_n0 + wave * Cfg::TN + (lane % Cfg::CPR) * 8;
+        // a piece = 32 rows x 128 columns of the output matrix: rows of C and the wave's 128 columns, or
+        // (XT) 32 of the wave's tokens = rows of Y and the block-row's 128 outputs
+        const int out_ld = XT ? M : N, out_rows = XT ? N : M, out_cols = XT ? M : N;
+        const int grow0 = (XT ? c_n0 + wave * Cfg::TN : c_br * BR) + lane / Cfg::CPR;
+        const int gcol0 = (XT ? c_br * BR : c_n0 + wave * Cfg::TN) + (lane % Cfg::CPR) * 8;
         const uint8_t *scl = sc + (lane / Cfg::CPR) * Cfg::C_PITCH + (lane % Cfg::CPR) * 16;
 #pragma unroll
-        for (int i = 0; i < MT; ++i) {
-            // fp32 -> bf16 (round to nearest even); lane holds row (lane & 31), 4 adjacent columns per q
+        for (int o = 0; o < 4; ++o) {
+            // fp32 -> bf16 (round to nearest even); lane holds row (lane & 31) of the piece, 4 adjacent columns per q
 #pragma unroll
-            for (int j = 0; j < NTL; ++j) {
-                f32x16 a = acc[i][j];
+            for (int in = 0; in < 4; ++in) {
+                f32x16 a = XT ? acc[in][o] : acc[o][in];
                 asm volatile("" : "+v"(a));  // the copy sits in vector registers before the clear overwrites
-                mfma_clear(i, j);
+                if (XT) mfma_clear(in, o);
+                else mfma_clear(o, in);
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     f32x4 v = {a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]};
                     bf16x4 hv = __builtin_convertvector(v, bf16x4);
-                    *(bf16x4 *)(sc + (lane & 31) * Cfg::C_PITCH + (j * 32 + 8 * q + 4 * (lane >> 5)) * 2) = hv;
+                    *(bf16x4 *)(sc + (lane & 31) * Cfg::C_PITCH + (in * 32 + 8 * q + 4 * (lane >> 5)) * 2) = hv;
                 }
             }
             // LDS is in order within a wave: the reads below see the writes above
-            uint16_t *cdst = C + (int64_t)(grow0 + i * 32) * N + gcol0;
+            uint16_t *cdst = C + (int64_t)(grow0 + o * 32) * out_ld + gcol0;
             if (interior) {
 #pragma unroll
                 for (int it = 0; it < 32 / Cfg::RPI; ++it) {
                     uint4 v = *(const uint4 *)(scl + it * Cfg::RPI * Cfg::C_PITCH);
-                    store_c16(cdst + (int64_t)it * Cfg::RPI * N, v);
+                    store_c16(cdst + (int64_t)it * Cfg::RPI * out_ld, v);
                 }
             } else {
 #pragma unroll
                 for (int it = 0; it < 32 / Cfg::RPI; ++it) {
                     uint4 v = *(const uint4 *)(scl + it * Cfg::RPI * Cfg::C_PITCH);
-                    if (grow0 + i * 32 + it * Cfg::RPI < M && gcol0 < N) store_c16(cdst + (int64_t)it * Cfg::RPI * N, v);
+                    if (grow0 + o * 32 + it * Cfg::RPI < out_rows && gcol0 < out_cols)
+                        store_c16(cdst + (int64_t)it * Cfg::RPI * out_ld, v);
                 }
             }
             ASP_FENCE();  // keeps the pieces apart: reading all 256 accumulators at once would spill
@@ -481,6 +557,8 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
 #undef ASP_WIDE_STEP
 #undef ASP_MFMA
 #undef ASP_MFMA_DMA
+#undef ASP_OP1
+#undef ASP_OP2
 #undef ASP_B_VOFF
 #undef ASP_B_BASE
 }
@@ -497,9 +575,8 @@ __global__ __launch_bounds__(256) void bcsr_clear_empty_rows_kernel(const int4 *
     for (int64_t i = (int64_t)blockIdx.y * 256 + threadIdx.x; i < n16; i += (int64_t)gridDim.y * 256) dst[i] = z;
 }
 
-// needs b_row = 128, bn = 512, N % 8 == 0, 8 <= N < 2^25 and 16-byte aligned B and C (the caller checked)
-bool bcsr_wide_launch(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream) {
-    if (h->b_row != 128 || p.bn != 512) return false;
+template <bool XT>
+static void launch_wide(const asp_handle *h, const void *B, void *C, int64_t N, int n_tiles, hipStream_t stream) {
     static const int env_group = [] {  // benchmarking switch only
         const char *e = std::getenv("ASP_BCSR_GROUP_N");
         return e ? std::atoi(e) : 0;
@@ -507,7 +584,32 @@ bool bcsr_wide_launch(const asp_handle *h, const void *B, void *C, int64_t N, co
     // two N-tiles walked together: an A block is fetched once per pair while the pair's slab of B (K x 1024)
     // still has a chance in the 4 MB of L2 (measured: 1, 3 and 4 are 3-10 % slower on the 90 %-sparse projection)
     int group_n = env_group > 0 ? env_group : 2;
-    if (group_n > p.n_tiles) group_n = p.n_tiles;
+    if (group_n > n_tiles) group_n = n_tiles;
+    const int64_t n_rows = h->hb.n_nonempty;
+    int64_t workers = h->n_cus;  // one resident workgroup per CU: the ring takes the whole LDS
+    if (workers > n_rows * n_tiles) workers = n_rows * n_tiles;
+    workers = std::max<int64_t>(8, workers / 8 * 8);  // the same number of workgroups on every XCD
+    static const int env_xcd = [] {  // benchmarking switch only: 0 = ignore the XCDs when dealing tiles
+        const char *e = std::getenv("ASP_BCSR_XCD_AWARE");
+        return e ? std::atoi(e) : 1;
+    }();
+    XcdRuns runs = cut_runs(h->hb.sorted_weight_prefix, n_rows, n_tiles, group_n);
+    if (!env_xcd)
+        for (int x = 1; x <= 8; ++x) runs.start[x] = runs.start[8];
+    dim3 grid((unsigned)workers), block(256);
+    if (h->k % 128 == 0)
+        hipLaunchKernelGGL((bcsr_spmm_wide_kernel<true, XT>), grid, block, 0, stream, (const int4 *)h->d_rank_info,
+                           h->d_col_idx, (const uint16_t *)h->d_values, (const uint16_t *)B, (uint16_t *)C, (int)h->m,
+                           (int)h->k, (int)N, (int)n_rows, (int)h->n_brows, (int)h->n_units, n_tiles, group_n, env_xcd, runs);
+    else
+        hipLaunchKernelGGL((bcsr_spmm_wide_kernel<false, XT>), grid, block, 0, stream, (const int4 *)h->d_rank_info,
+                           h->d_col_idx, (const uint16_t *)h->d_values, (const uint16_t *)B, (uint16_t *)C, (int)h->m,
+                           (int)h->k, (int)N, (int)n_rows, (int)h->n_brows, (int)h->n_units, n_tiles, group_n, env_xcd, runs);
+}
+
+// needs b_row = 128, bn = 512, N % 8 == 0, 8 <= N < 2^25 and 16-byte aligned B and C (the caller checked)
+bool bcsr_wide_launch(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream) {
+    if (h->b_row != 128 || p.bn != 512) return false;
     const int64_t n_rows = h->hb.n_nonempty, n_empty = h->n_brows - n_rows;
     if (n_empty > 0 && n_rows == 0) {  // nothing to multiply: the clearing is all there is
         dim3 grid((unsigned)n_empty, 16), block(256);
@@ -515,26 +617,90 @@ bool bcsr_wide_launch(const asp_handle *h, const void *B, void *C, int64_t N, co
                            (uint16_t *)C, (int)h->m, (int)N, 128);
     }
     if (n_rows == 0) return true;
-    int64_t workers = h->n_cus;  // one resident workgroup per CU: the ring takes the whole LDS
-    if (workers > n_rows * p.n_tiles) workers = n_rows * p.n_tiles;
-    workers = std::max<int64_t>(8, workers / 8 * 8);  // the same number of workgroups on every XCD
-    static const int env_xcd = [] {  // benchmarking switch only: 0 = ignore the XCDs when dealing tiles
-        const char *e = std::getenv("ASP_BCSR_XCD_AWARE");
-        return e ? std::atoi(e) : 1;
-    }();
-    XcdRuns runs = cut_runs(h->hb.sorted_weight_prefix, n_rows, p.n_tiles, group_n);
-    if (!env_xcd)
-        for (int x = 1; x <= 8; ++x) runs.start[x] = runs.start[8];
-    dim3 grid((unsigned)workers), block(256);
-    if (h->k % 128 == 0)
-        hipLaunchKernelGGL(bcsr_spmm_wide_kernel<true>, grid, block, 0, stream, (const int4 *)h->d_rank_info,
-                           h->d_col_idx, (const uint16_t *)h->d_values, (const uint16_t *)B, (uint16_t *)C, (int)h->m,
-                           (int)h->k, (int)N, (int)n_rows, (int)h->n_brows, (int)h->n_units, p.n_tiles, group_n, env_xcd, runs);
-    else
-        hipLaunchKernelGGL(bcsr_spmm_wide_kernel<false>, grid, block, 0, stream, (const int4 *)h->d_rank_info,
-                           h->d_col_idx, (const uint16_t *)h->d_values, (const uint16_t *)B, (uint16_t *)C, (int)h->m,
-                           (int)h->k, (int)N, (int)n_rows, (int)h->n_brows, (int)h->n_units, p.n_tiles, group_n, env_xcd, runs);
+    launch_wide<false>(h, B, C, N, p.n_tiles, stream);
     return true;
+}
+
+// ---- Y = X x A^T with K-contiguous X and Y (Section IV-D's layout) -------------------------------------
+
+// Any block size, any alignment, any N: one thread per (token, quarter of the block-row's outputs), fp32
+// multiply-adds over the stored blocks in order.  The safety net under the MFMA path below; two orders of
+// magnitude slower.  grid = (block-rows, ceil(N / 64)), 256 threads.
+template <int BR>
+__global__ __launch_bounds__(256) void bcsr_xt_generic_kernel(const int32_t *__restrict__ block_row_ptr,
+                                                              const int32_t *__restrict__ block_col_idx,
+                                                              const uint16_t *__restrict__ a_packed,
+                                                              const uint16_t *__restrict__ X, uint16_t *__restrict__ Y,
+                                                              int M, int K, int64_t N) {
+    constexpr int RPT = BR / 4;  // outputs per thread
+    const int br = blockIdx.x, rg = threadIdx.x >> 6;
+    const int64_t n = (int64_t)blockIdx.y * 64 + (threadIdx.x & 63);
+    if (n >= N) return;
+    float acc[RPT];
+#pragma unroll
+    for (int r = 0; r < RPT; ++r) acc[r] = 0.f;
+    const uint16_t *x = X + n * K;
+    for (int p = block_row_ptr[br]; p < block_row_ptr[br + 1]; ++p) {
+        const int k0 = block_col_idx[p] * BR;
+        const uint16_t *blk = a_packed + (int64_t)p * BR * BR;
+        for (int k = 0; k < BR && k0 + k < K; ++k) {
+            const float xv = __uint_as_float((uint32_t)x[k0 + k] << 16);
+#pragma unroll
+            for (int r = 0; r < RPT; ++r) {
+                const int row = rg * RPT + r;
+                // fragment order: [16-wide k slice][group of 32 rows][lane = row % 32 + 32 * (k % 16 / 8)][k % 8]
+                const int idx = (((k >> 4) * (BR / 32) + (row >> 5)) * 64 + (row & 31) + 32 * ((k & 15) >> 3)) * 8 + (k & 7);
+                acc[r] = fmaf(__uint_as_float((uint32_t)blk[idx] << 16), xv, acc[r]);
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < RPT; ++r) {
+        const int m = br * BR + rg * RPT + r;
+        if (m < M) {
+            // round to nearest even (inputs are finite sums; NaN payloads are not preserved)
+            uint32_t u = __float_as_uint(acc[r]);
+            u += 0x7FFFu + ((u >> 16) & 1u);
+            Y[n * M + m] = (uint16_t)(u >> 16);
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void bcsr_fill_zero_kernel(uint16_t *__restrict__ p, int64_t n) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = 0;
+}
+
+asp_status_t bcsr_spmm_xt_launch(const asp_handle *h, const void *X, void *Y, int64_t N, hipStream_t stream) {
+    const int64_t n_rows = h->hb.n_nonempty;
+    if (n_rows == 0) {
+        hipLaunchKernelGGL(bcsr_fill_zero_kernel, dim3(1024), dim3(256), 0, stream, (uint16_t *)Y, N * h->m);
+    } else {
+        const bool aligned = (((uintptr_t)X | (uintptr_t)Y) & 15) == 0;
+        const int64_t cus = h->n_cus > 0 ? h->n_cus : 256;
+        const int64_t n_tiles = ceil_div(N, 512);
+        // benchmarking switch only: ASP_BCSR_XT=generic forces the fallback
+        static const bool force_generic = [] {
+            const char *e = std::getenv("ASP_BCSR_XT");
+            return e && std::strcmp(e, "generic") == 0;
+        }();
+        if (!force_generic && h->b_row == 128 && aligned && h->k % 8 == 0 && h->m % 8 == 0 && N < (1ll << 25) &&
+            h->k < (1ll << 22) && n_rows * n_tiles >= cus) {
+            launch_wide<true>(h, X, Y, N, (int)n_tiles, stream);
+        } else {
+            dim3 grid((unsigned)h->n_brows, (unsigned)ceil_div(N, 64)), block(256);
+            if (grid.y > 65535) return fail(ASP_ERR_UNSUPPORTED, "N too large for the generic K-contiguous path");
+#define ASP_XT_GENERIC(BR)                                                                                          \
+    hipLaunchKernelGGL(bcsr_xt_generic_kernel<BR>, grid, block, 0, stream, h->d_row_ptr, h->d_col_idx,              \
+                       (const uint16_t *)h->d_values, (const uint16_t *)X, (uint16_t *)Y, (int)h->m, (int)h->k, N)
+            if (h->b_row == 128) ASP_XT_GENERIC(128);
+            else if (h->b_row == 64) ASP_XT_GENERIC(64);
+            else ASP_XT_GENERIC(32);
+#undef ASP_XT_GENERIC
+        }
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ASP_ERR_HIP, std::string("BCSR K-contiguous kernel launch: ") + hipGetErrorString(e));
+    return ASP_OK;
 }
 
 }  // namespace asp

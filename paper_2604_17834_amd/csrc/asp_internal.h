@@ -95,6 +95,7 @@ BcsrPlan bcsr_plan(const asp_handle *h, int64_t N, bool aligned);
 bool bcsr_dma_launch(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream);
 bool bcsr_wide_launch(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream);
 asp_status_t bcsr_spmm_launch(const asp_handle *h, const void *B, void *C, int64_t N, hipStream_t stream);
+asp_status_t bcsr_spmm_xt_launch(const asp_handle *h, const void *X, void *Y, int64_t N, hipStream_t stream);
 
 struct WcsrPlan {
     int32_t bn;

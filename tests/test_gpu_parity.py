@@ -237,6 +237,72 @@ def test_bcsr_wide_tiles_times_identity_is_A_bit_exact():
     dense[dense == 0x8000] = 0  # a stored -0.0 times 1.0, added to the +0.0 the sum starts from, is +0.0
     assert np.array_equal(C, dense)
 
+
+# ---- K-contiguous entry: Y[N x m] = X[N x k] x A^T (Section IV-D's layout) -----------------------------------
+def gpu_spmm_xt(a: synth.Csr, b, X: np.ndarray, misalign=False):
+    h = asp.asp_create_from_csr("bcsr", a.dtype, b, b, a.m, a.k, a.row_ptr, a.col_idx, a.values)
+    try:
+        N = X.shape[0]
+        if misalign:
+            Xf = torch.empty(X.size + 1, dtype=torch.int16, device="cuda")
+            Xd = Xf[1:].view(X.shape)
+            Xd.copy_(_dev_in(np.ascontiguousarray(X)))
+            Yf = torch.empty(N * a.m + 1, dtype=torch.int16, device="cuda")
+            Yd = Yf[1:].view(N, a.m)
+        else:
+            Xd = _dev_in(np.ascontiguousarray(X))
+            Yd = torch.empty((N, a.m), dtype=torch.int16, device="cuda")
+        Yd.fill_(0x7FC1)  # poison: every element must be overwritten
+        asp.asp_spmm_xt(h, Xd.data_ptr(), Yd.data_ptr(), N, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        return Yd.cpu().numpy().view(np.uint16)
+    finally:
+        asp.asp_destroy(h)
+
+
+@pytest.mark.parametrize("m,k,N,sparsity", [
+    (40 * 128, 5 * 128, 8 * 512, 0.5),                # aligned everywhere: the MFMA path
+    (40 * 128 + 40, 5 * 128 + 24, 8 * 512 - 13, 0.5),  # ragged M, K (chunks past K) and a token tail
+    (72 * 128, 128, 7 * 512, 0.2),                    # single-block tiles
+    (64 * 128 + 8, 9 * 128, 4096, 0.85),              # empty block-rows: their outputs are zero in every row of Y
+])
+def test_bcsr_xt_matrix_core_path_parity(m, k, N, sparsity):
+    a = synth.block_sparse_bernoulli(m, k, 128, 128, sparsity, seed=41, dtype="bf16")
+    X = synth.dense_normal(N, k, "bf16", seed=42)
+    Y = gpu_spmm_xt(a, 128, X)
+    # the definition: Y^T = A x X^T
+    check_against_oracle(a, np.ascontiguousarray(X.T), np.ascontiguousarray(Y.T))
+
+
+@pytest.mark.parametrize("b", [32, 64, 128])
+@pytest.mark.parametrize("m,k,N,misalign", [(300, 200, 77, False), (256, 256, 64, True), (130, 96, 1, False)])
+def test_bcsr_xt_generic_path_parity(b, m, k, N, misalign):
+    a = synth.random_csr(m, k, 0.05, seed=43 + b, dtype="bf16", dist="normal", empty_row_frac=0.3)
+    X = synth.dense_normal(N, k, "bf16", seed=44)
+    Y = gpu_spmm_xt(a, b, X, misalign=misalign)
+    check_against_oracle(a, np.ascontiguousarray(X.T), np.ascontiguousarray(Y.T))
+
+
+def test_bcsr_xt_equals_transposed_spmm_bitwise():
+    # both entries run the same multiply-add sequence per output on the matrix cores
+    m, k, N = 48 * 128, 6 * 128, 4096
+    a = synth.block_sparse_bernoulli(m, k, 128, 128, 0.6, seed=45, dtype="bf16")
+    X = synth.dense_normal(N, k, "bf16", seed=46)
+    Y = gpu_spmm_xt(a, 128, X)
+    C = gpu_spmm(a, "bcsr", 128, 128, np.ascontiguousarray(X.T))
+    assert np.array_equal(Y, C.T)
+
+
+def test_bcsr_xt_rejects_wcsr_handles():
+    a = synth.random_csr(64, 64, 0.1, seed=47, dtype="f32")
+    h = asp.asp_create_from_csr("wcsr", "f32", 16, 8, a.m, a.k, a.row_ptr, a.col_idx, a.values)
+    try:
+        x = torch.zeros((8, 64), dtype=torch.float32, device="cuda")
+        y = torch.zeros((8, 64), dtype=torch.float32, device="cuda")
+        assert asp.asp_spmm_xt(h, x.data_ptr(), y.data_ptr(), 8, None, check=False) == asp.ASP_ERR_UNSUPPORTED
+    finally:
+        asp.asp_destroy(h)
+
 # ------------------------------------------------------------------ WCSR
 @pytest.mark.parametrize("b_row", [16, 32, 64])
 @pytest.mark.parametrize("m,k,N,density,task_cols", [

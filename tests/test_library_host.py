@@ -177,3 +177,15 @@ def test_plan_follows_tile_width_rule():
             assert p.bn == oracle.choose_bn(N, cands), (N, p.bn)
     finally:
         asp.asp_destroy(h)
+
+
+def test_spmm_entries_refuse_host_only_handles_and_null_pointers():
+    a = synth.block_sparse_bernoulli(256, 256, 128, 128, 0.5, 3)
+    h = asp.asp_create_from_csr("bcsr", "bf16", 128, 128, a.m, a.k, a.row_ptr, a.col_idx, a.values, flags=HOST)
+    try:
+        for fn in (asp.asp_spmm, asp.asp_spmm_xt):
+            assert fn(h, 16, 32, 64, None, check=False) == asp.ASP_ERR_UNSUPPORTED   # no device arrays
+            assert fn(h, None, 32, 64, None, check=False) == asp.ASP_ERR_INVALID_ARG
+            assert fn(h, 16, 32, 0, None, check=False) == asp.ASP_ERR_INVALID_ARG
+    finally:
+        asp.asp_destroy(h)
