@@ -21,6 +21,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3     # MI355X fp32 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 # the paper's numbers (NVIDIA H100, other hardware: context only)
@@ -66,7 +67,7 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
         Cd = torch.empty((N, a.m) if xt else (a.m, N), dtype=torch.int16, device="cuda")
     else:
         Bd = torch.from_numpy(B).cuda()
-        Cd = torch.empty((a.m, N), dtype=torch.float32, device="cuda")
+        Cd = torch.empty((N, a.m) if xt else (a.m, N), dtype=torch.float32, device="cuda")
     bp, cp = Bd.data_ptr(), Cd.data_ptr()
 
     for _ in range(warmup):
@@ -91,11 +92,11 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
         # work per stored block: 2*b_row*b_col*N flop (Section II-C: zeros inside blocks are computed)
         flops_alg = 2.0 * info.n_units * b_row * b_col * N
         bytes_alg = info.n_units * b_row * b_col * esz + a.k * N * esz + a.m * N * esz
-        roof = {"bound": "mfma", "achieved": flops_alg / (kern_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s"}
+        peak = PEAK_BF16_TFLOPS if dt == "bf16" else PEAK_F32_TFLOPS
+        roof = {"bound": "mfma", "achieved": flops_alg / (kern_ms * 1e-3) / 1e12, "peak": peak, "unit": "TFLOP/s"}
         extra = {"stored_blocks": int(info.n_units), "algorithmic_bytes": int(bytes_alg),
                  "hbm_floor_ms": bytes_alg / (PEAK_HBM_GBS * 1e9) * 1e3,
-                 "mfma_floor_ms": flops_alg / (PEAK_BF16_TFLOPS * 1e12) * 1e3}
+                 "mfma_floor_ms": flops_alg / (peak * 1e12) * 1e3}
     else:
         wci = asp.asp_export(h, asp.ASP_ARR_COL_IDX)
         tasks = asp.asp_export(h, asp.ASP_ARR_TASKS)
@@ -103,7 +104,7 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
         split_windows = int(len(np.unique(tasks[tasks[:, 3] != 0, 0]))) if len(tasks) else 0
         # per packed column: b_row values + 1 index of A, one gathered B row; per window one C tile
         # (split windows: cleared, then read-modify-written by every task -- counted as 2 extra passes)
-        bytes_alg = (info.n_units * (b_row * 4 + 4) + real_cols * N * 4 + a.m * N * 4
+        bytes_alg = (info.n_units * (b_row * esz + 4) + real_cols * N * esz + a.m * N * esz
                      + 2 * split_windows * b_row * N * 4)
         roof = {"bound": "hbm", "achieved": bytes_alg / (kern_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
         extra = {"packed_cols": int(info.n_units), "real_cols": real_cols, "tasks": int(info.n_tasks),
@@ -115,7 +116,7 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
     roof["kernel_ms_median"] = float(np.median(per))
 
     res = {
-        "workload": name, "format": fmt, "b_row": b_row, "b_col": b_col, "m": a.m, "k": a.k, "N": N, "nnz": a.nnz,
+        "workload": name, "format": fmt, "dtype": dt, "b_row": b_row, "b_col": b_col, "m": a.m, "k": a.k, "N": N, "nnz": a.nnz,
         "fill_ratio": info.fill_ratio, "bn": plan.bn, "workgroups": int(plan.workgroups),
         "value": flops_eff / (wall_ms * 1e-3) / 1e9, "ms_per_step": wall_ms, "roofline": roof,
         "convert_s": t_convert, "generate_s": t_gen, **extra,
@@ -237,7 +238,7 @@ def main():
                   if args.workload == "bcsr_gate_proj" else "effective SpMM GFLOP/s (2*nnz*N/t)",
         "value": main_res["value"], "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if main_res["format"] == "bcsr" else "f32", "data": "synthetic",
+        "dtype": main_res["dtype"], "data": "synthetic",
         "config": {"workload": args.workload, **{k: main_res[k] for k in
                                                    ("format", "b_row", "b_col", "m", "k", "N", "nnz", "bn", "workgroups")}},
         "roofline": main_res["roofline"],

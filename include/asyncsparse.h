@@ -50,7 +50,7 @@ typedef enum { ASP_DT_BF16 = 0, ASP_DT_F32 = 1 } asp_dtype_t;
 
 typedef struct {
     int32_t format;    /* asp_format_t */
-    int32_t dtype;     /* asp_dtype_t; supported pairs: BCSR+bf16, WCSR+f32 */
+    int32_t dtype;     /* asp_dtype_t; supported pairs: BCSR+bf16, BCSR+f32, WCSR+f32 */
     int32_t b_row;     /* BCSR: block height in {32,64,128}; WCSR: window height in {16,32,64} */
     int32_t b_col;     /* BCSR: block width, = b_row; WCSR: column padding unit, = 8 */
     int32_t task_cols; /* WCSR: packed columns per sub-task, positive multiple of b_col; 0 = default (512) */
@@ -112,6 +112,7 @@ asp_status_t asp_create_from_csr(const asp_config_t *cfg, int64_t m, int64_t k, 
  * fully overwritten (rows of A without entries become zeros); C must not alias B.
  * N >= 1.  stream: hipStream_t (NULL = default).  Asynchronous: only enqueues kernels, never
  * synchronises, never allocates.  bf16: fp32 accumulation, round-to-nearest-even to bf16 on store.
+ * f32: fp32 products and sums on the matrix cores (no reduced-precision operand formats).
  * f32 WCSR: windows that are split into several tasks are combined with fp32 atomic adds, so their
  * rows may differ in the last bits from run to run; everything else is bitwise reproducible.
  */

@@ -57,7 +57,10 @@ static asp_status_t create_impl(const asp_config_t *cfg, int64_t m, int64_t k, i
         csr_to_bcsr(m, k, row_ptr, col_idx, values, es, cfg->b_row, cfg->b_col, h->hb);
         h->n_units = (int64_t)h->hb.block_col_idx.size();
         if (host_only) return ASP_OK;
-        bcsr_pack_fragments_bf16(h->hb, cfg->b_row, cfg->b_col, h->hb.packed);
+        if (cfg->dtype == ASP_DT_F32)
+            bcsr_pack_fragments_f32(h->hb, cfg->b_row, cfg->b_col, h->hb.packed);
+        else
+            bcsr_pack_fragments_bf16(h->hb, cfg->b_row, cfg->b_col, h->hb.packed);
         ASP_HIP_TRY(hipGetDevice(&h->device));
         asp_status_t s;
         if ((s = upload(&h->d_row_ptr, h->hb.block_row_ptr.data(), h->hb.block_row_ptr.size() * 4, stream))) return s;
@@ -112,7 +115,7 @@ asp_status_t asp_create_from_csr(const asp_config_t *cfg, int64_t m, int64_t k, 
     if (nnz > 0 && (!col_idx || !values)) return fail(ASP_ERR_INVALID_ARG, "null col_idx or values with nnz > 0");
     if (cfg->flags & ~ASP_FLAG_HOST_CONVERT_ONLY) return fail(ASP_ERR_INVALID_ARG, "unknown flag bits");
     if (cfg->format == ASP_FMT_BCSR) {
-        if (cfg->dtype != ASP_DT_BF16) return fail(ASP_ERR_UNSUPPORTED, "BCSR is built for bf16 only");
+        if (cfg->dtype != ASP_DT_BF16 && cfg->dtype != ASP_DT_F32) return fail(ASP_ERR_INVALID_ARG, "unknown dtype");
         if (!(cfg->b_row == 32 || cfg->b_row == 64 || cfg->b_row == 128) || cfg->b_col != cfg->b_row)
             return fail(ASP_ERR_UNSUPPORTED, "BCSR blocks must be 32x32, 64x64 or 128x128");
     } else if (cfg->format == ASP_FMT_WCSR) {
@@ -163,7 +166,8 @@ asp_status_t asp_spmm_xt(const asp_handle_t *h, const void *X, void *Y, int64_t 
     if (!h || !X || !Y) return fail(ASP_ERR_INVALID_ARG, "null handle, X or Y");
     if (N < 1) return fail(ASP_ERR_INVALID_ARG, "N must be >= 1");
     if (h->device < 0) return fail(ASP_ERR_UNSUPPORTED, "handle was converted on the host only; it has no device arrays");
-    if (h->format != ASP_FMT_BCSR) return fail(ASP_ERR_UNSUPPORTED, "the K-contiguous entry is built for BCSR handles only");
+    if (h->format != ASP_FMT_BCSR || h->dtype != ASP_DT_BF16)
+        return fail(ASP_ERR_UNSUPPORTED, "the K-contiguous entry is built for bf16 BCSR handles only");
     if (N >= (1ll << 31) || h->m * N >= (1ll << 40) || h->k * N >= (1ll << 40)) return fail(ASP_ERR_UNSUPPORTED, "N too large");
     return bcsr_spmm_xt_launch(h, X, Y, N, (hipStream_t)stream);
 }

@@ -254,6 +254,14 @@ static int choose_bn(int64_t N, const int *cand, int n) {
 
 BcsrPlan bcsr_plan(const asp_handle *h, int64_t N, bool aligned) {
     BcsrPlan p;
+    if (h->dtype == ASP_DT_F32) {  // fp32 kernel: 128- and 256-wide tiles, element-wise path at 128
+        static const int cand32[2] = {128, 256};
+        p.vectorized = (aligned && N % 4 == 0) ? 1 : 0;
+        p.bn = p.vectorized ? choose_bn(N, cand32, 2) : 128;
+        p.n_tiles = (int32_t)ceil_div(N, p.bn);
+        p.workgroups = h->n_brows * p.n_tiles;
+        return p;
+    }
     p.vectorized = (aligned && N % 8 == 0) ? 1 : 0;
     static const int cand[4] = {64, 128, 256, 512};
     // benchmarking switch only: ASP_BCSR_BN caps the tile width (it must be one of the built widths)
@@ -295,6 +303,13 @@ asp_status_t bcsr_spmm_launch(const asp_handle *h, const void *B, void *C, int64
     const bool aligned = (((uintptr_t)B | (uintptr_t)C) & 15) == 0;
     const BcsrPlan p = bcsr_plan(h, N, aligned);
     if (p.workgroups * 8 >= (1ll << 31)) return fail(ASP_ERR_UNSUPPORTED, "too many output tiles");
+    if (h->dtype == ASP_DT_F32) {
+        if (!bcsr_f32_launch(h, B, C, N, p, stream))
+            return fail(ASP_ERR_UNSUPPORTED, "no fp32 kernel for this block size / tile width");
+        hipError_t e32 = hipGetLastError();
+        if (e32 != hipSuccess) return fail(ASP_ERR_HIP, std::string("BCSR fp32 kernel launch: ") + hipGetErrorString(e32));
+        return ASP_OK;
+    }
     const int key = h->b_row * 1000 + p.bn;
     // benchmarking switch only: ASP_BCSR_KERNEL=regstage selects the synchronous-copy kernel
     static const bool force_regstage = [] {

@@ -209,6 +209,32 @@ void bcsr_pack_fragments_bf16(const HostBcsr &in, int32_t b_row, int32_t b_col, 
     });
 }
 
+// Kernel-internal order of an fp32 block: for each 16-wide k slice, each group of 32 rows and each group of
+// 8 k, lane l of a wavefront holds the 4 values A[l % 32][2t + l / 32], t = 0..3: the A operands of four
+// consecutive v_mfma_f32_32x32x2_f32 (lane l feeds row l % 32, k index l / 32).  A pure permutation.
+void bcsr_pack_fragments_f32(const HostBcsr &in, int32_t b_row, int32_t b_col, std::vector<uint8_t> &packed) {
+    const int64_t nb = (int64_t)in.block_col_idx.size();
+    const int64_t bsz = (int64_t)b_row * b_col;
+    packed.resize(in.blocks.size());
+    const uint32_t *src = (const uint32_t *)in.blocks.data();
+    uint32_t *dst = (uint32_t *)packed.data();
+    const int32_t mtiles = b_row / 32, kslices = b_col / 16;
+    parallel_chunks(nb, 4, [&](unsigned, int64_t b, int64_t e) {
+        for (int64_t q = b; q < e; ++q) {
+            const uint32_t *s = src + q * bsz;
+            uint32_t *d = dst + q * bsz;
+            for (int32_t ks = 0; ks < kslices; ++ks)
+                for (int32_t mt = 0; mt < mtiles; ++mt)
+                    for (int32_t kg = 0; kg < 2; ++kg)
+                        for (int32_t lane = 0; lane < 64; ++lane)
+                            for (int32_t t = 0; t < 4; ++t) {
+                                int32_t row = mt * 32 + lane % 32, col = ks * 16 + kg * 8 + 2 * t + lane / 32;
+                                *d++ = s[(int64_t)row * b_col + col];
+                            }
+        }
+    });
+}
+
 // ------------------------------------------------------------------------------------------ WCSR
 namespace {
 

@@ -52,6 +52,7 @@ void csr_to_bcsr(int64_t m, int64_t k, const int32_t *row_ptr, const int32_t *co
                  size_t esize, int32_t b_row, int32_t b_col, HostBcsr &out);
 void bcsr_build_schedule(HostBcsr &b);
 void bcsr_pack_fragments_bf16(const HostBcsr &in, int32_t b_row, int32_t b_col, std::vector<uint8_t> &packed);
+void bcsr_pack_fragments_f32(const HostBcsr &in, int32_t b_row, int32_t b_col, std::vector<uint8_t> &packed);
 void csr_to_wcsr(int64_t m, int64_t k, const int32_t *row_ptr, const int32_t *col_idx, const void *values,
                  size_t esize, int32_t b_row, int32_t b_col, HostWcsr &out);
 void wcsr_tasks_host(const std::vector<int32_t> &window_row_ptr, int32_t task_cols, std::vector<int32_t> &tasks);
@@ -93,6 +94,7 @@ struct BcsrPlan {
 };
 BcsrPlan bcsr_plan(const asp_handle *h, int64_t N, bool aligned);
 bool bcsr_dma_launch(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream);
+bool bcsr_f32_launch(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream);
 bool bcsr_wide_launch(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream);
 asp_status_t bcsr_spmm_launch(const asp_handle *h, const void *B, void *C, int64_t N, hipStream_t stream);
 asp_status_t bcsr_spmm_xt_launch(const asp_handle *h, const void *X, void *Y, int64_t N, hipStream_t stream);

@@ -218,23 +218,31 @@ def banded_plus_dense_rows(m: int, seed: int, half_band: int = 13, n_dense_rows:
 # named workloads (BASELINE configs).  `scale` < 1 shrinks them for tests.
 # --------------------------------------------------------------------------
 def workload(name: str, scale: float = 1.0):
-    """Return (csr, format, b_row, b_col, N, dtype, seedB) for a named workload."""
+    """Return (csr, format, b_row, b_col, N, dtype, seedB) for a named workload.
+
+    A suffix "_f32" or "_bf16" gives the same structure and the same random draws stored in the other
+    precision (the dtype x format cross product; BCSR workloads default to bf16, WCSR ones to f32).
+    """
     s = scale
+    dt = None
+    for suffix, d in (("_f32", F32), ("_bf16", BF16)):
+        if name.endswith(suffix):
+            name, dt = name[:-len(suffix)], d
     if name == "bcsr_small":            # config 1
-        a = block_sparse_bernoulli(1024, 1024, 64, 64, 0.90, seed=1001)
-        return a, "bcsr", 64, 64, 256, BF16, 1004
+        a = block_sparse_bernoulli(1024, 1024, 64, 64, 0.90, seed=1001, dtype=dt or BF16)
+        return a, "bcsr", 64, 64, 256, dt or BF16, 1004
     if name == "bcsr_gate_proj":        # config 2 (gate/up projection)
-        a = block_sparse_bernoulli(18944, 3584, 128, 128, 0.90, seed=1002)
-        return a, "bcsr", 128, 128, max(256, int(16384 * s)), BF16, 1005
+        a = block_sparse_bernoulli(18944, 3584, 128, 128, 0.90, seed=1002, dtype=dt or BF16)
+        return a, "bcsr", 128, 128, max(256, int(16384 * s)), dt or BF16, 1005
     if name == "bcsr_down_proj":        # config 2 (down projection)
-        a = block_sparse_bernoulli(3584, 18944, 128, 128, 0.90, seed=1012)
-        return a, "bcsr", 128, 128, max(256, int(16384 * s)), BF16, 1015
+        a = block_sparse_bernoulli(3584, 18944, 128, 128, 0.90, seed=1012, dtype=dt or BF16)
+        return a, "bcsr", 128, 128, max(256, int(16384 * s)), dt or BF16, 1015
     if name == "wcsr_zipf":             # config 3
         m = max(1024, int((1 << 20) * s))
-        a = zipf_graph(m, m, 16 * m, seed=1003)
-        return a, "wcsr", 16, 8, 128, F32, 1006
+        a = zipf_graph(m, m, 16 * m, seed=1003, dtype=dt or F32)
+        return a, "wcsr", 16, 8, 128, dt or F32, 1006
     if name == "wcsr_band_dense_rows":  # config 4
         m = max(4096, int(2_000_000 * s))
-        a = banded_plus_dense_rows(m, seed=1004, dense_row_nnz=max(64, int(200000 * s)))
-        return a, "wcsr", 16, 8, 64, F32, 1007
+        a = banded_plus_dense_rows(m, seed=1004, dense_row_nnz=max(64, int(200000 * s)), dtype=dt or F32)
+        return a, "wcsr", 16, 8, 64, dt or F32, 1007
     raise KeyError(name)

@@ -411,3 +411,48 @@ def test_wcsr_config4_reduced_band_plus_dense_rows():
         C = gpu_spmm(a, fmt, br, bc, B)
         cols = None if N == 64 else np.arange(96, 160)
         check_against_oracle(a, B, C, cols)
+
+
+# ------------------------------------------------------------------ BCSR in fp32 (both formats at one precision)
+@pytest.mark.parametrize("b", [32, 64, 128])
+@pytest.mark.parametrize("m,k,N,sparsity", [
+    (256, 256, 256, 0.5),     # several tiles, widest tile
+    (384, 512, 128, 0.7),
+    (300, 200, 384, 0.6),     # ragged M and K; N = 3 x 128
+    (256, 384, 200, 0.5),     # masked N tail on the 16-byte path (200 % 4 == 0)
+    (160, 288, 101, 0.5),     # N % 4 != 0: element-wise path
+    (128, 256, 1, 0.3),
+])
+def test_bcsr_f32_parity(b, m, k, N, sparsity):
+    a = synth.block_sparse_bernoulli(m, k, b, b, sparsity, seed=300 + b + N, dtype="f32", std=1.0)
+    B = synth.dense_normal(k, N, "f32", seed=9 + N)
+    C = gpu_spmm(a, "bcsr", b, b, B)
+    check_against_oracle(a, B, C)
+
+
+@pytest.mark.parametrize("b", [32, 64, 128])
+def test_bcsr_f32_scattered_entries_identity_and_misalignment(b):
+    a = synth.random_csr(520, 390, 0.004, seed=40 + b, dtype="f32", empty_row_frac=0.3, dist="normal")
+    B = synth.dense_normal(a.k, 132, "f32", seed=2)
+    C = gpu_spmm(a, "bcsr", b, b, B)
+    check_against_oracle(a, B, C)
+    assert not C[np.diff(a.row_ptr) == 0].any()      # rows without entries: exactly +0
+    check_against_oracle(a, B, gpu_spmm(a, "bcsr", b, b, B, misalign=True))
+    # products with 1.0 and sums with 0.0 are exact: A x I must be A's bits (a stored -0.0 adds up to +0.0)
+    Ci = gpu_spmm(a, "bcsr", b, b, synth.dense_identity(a.k, "f32"))
+    dense = np.zeros((a.m, a.k), np.float32)
+    for i in range(a.m):
+        dense[i, a.col_idx[a.row_ptr[i]:a.row_ptr[i + 1]]] = a.values[a.row_ptr[i]:a.row_ptr[i + 1]]
+    assert np.array_equal(Ci.view(np.uint32), (dense + np.float32(0)).view(np.uint32))
+
+
+def test_bcsr_f32_geometric_rows_sampled_and_rerun_bitwise():
+    a = synth.block_sparse_geometric(2048, 2048, 128, 128, 0.9, seed=77, dtype="f32", std=1.0)
+    B = synth.dense_normal(a.k, 1024, "f32", seed=78)
+    h = asp.asp_create_from_csr("bcsr", "f32", 128, 128, a.m, a.k, a.row_ptr, a.col_idx, a.values)
+    try:
+        C1 = gpu_spmm(a, "bcsr", 128, 128, B, handle=h)
+        assert np.array_equal(C1, gpu_spmm(a, "bcsr", 128, 128, B, handle=h))
+    finally:
+        asp.asp_destroy(h)
+    check_against_oracle(a, B, C1, _sample_columns(1024, 256, np.random.default_rng(3)))

@@ -46,7 +46,8 @@ def test_argument_and_csr_errors():
     assert ok == asp.ASP_OK
     assert _create_status("bcsr", "bf16", 48, 48, 2, 2, rp, ci, bf) == asp.ASP_ERR_UNSUPPORTED
     assert _create_status("bcsr", "bf16", 64, 32, 2, 2, rp, ci, bf) == asp.ASP_ERR_UNSUPPORTED
-    assert _create_status("bcsr", "f32", 64, 64, 2, 2, rp, ci, f32) == asp.ASP_ERR_UNSUPPORTED
+    assert _create_status("bcsr", "f32", 64, 64, 2, 2, rp, ci, f32) == asp.ASP_OK
+    assert _create_status("bcsr", 5, 64, 64, 2, 2, rp, ci, f32) == asp.ASP_ERR_INVALID_ARG     # unknown dtype
     assert _create_status("wcsr", "f32", 16, 4, 2, 2, rp, ci, f32) == asp.ASP_ERR_UNSUPPORTED
     assert _create_status("wcsr", "f32", 16, 8, 2, 2, rp, ci, f32, task_cols=12) == asp.ASP_ERR_INVALID_ARG
     assert _create_status(7, "f32", 16, 8, 2, 2, rp, ci, f32) == asp.ASP_ERR_INVALID_ARG
@@ -97,6 +98,25 @@ def test_bcsr_converter_bit_exact_vs_oracle(m, k, br, density):
         info = asp.asp_get_info(h)
         assert (info.n_brows, info.n_units, info.nnz) == (len(brp) - 1, len(bci), a.nnz)
         assert info.fill_ratio == oracle.fill_ratio(a.nnz, len(bci), br, br)
+    finally:
+        asp.asp_destroy(h)
+
+
+@pytest.mark.parametrize("m,k,br,density", [(200, 130, 32, 0.02), (129, 257, 64, 0.01), (300, 300, 128, 0.005)])
+def test_bcsr_f32_converter_bit_exact_vs_oracle(m, k, br, density):
+    a = synth.random_csr(m, k, density, 6, "f32", empty_row_frac=0.2, dist="normal")
+    h = asp.asp_create_from_csr("bcsr", "f32", br, br, m, k, a.row_ptr, a.col_idx, a.values, flags=HOST)
+    try:
+        brp, bci, blocks = oracle.to_bcsr(m, k, a.row_ptr, a.col_idx, a.values, "f32", br, br)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_ROW_PTR), brp)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_COL_IDX), bci)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_VALUES).view(np.uint32).ravel(), blocks.view(np.uint32).ravel())
+        assert asp.asp_get_info(h).fill_ratio == oracle.fill_ratio(a.nnz, len(bci), br, br)
+        for N in (128, 256, 384, 1024, 200, 101, 1):   # fp32 kernel: 128- and 256-wide tiles, element-wise at 128
+            p = asp.asp_plan_spmm(h, N)
+            assert p.vectorized == (1 if N % 4 == 0 else 0)
+            assert p.bn == (oracle.choose_bn(N, [128, 256]) if N % 4 == 0 else 128)
+            assert p.n_tiles == -(-N // p.bn) and p.workgroups == (len(brp) - 1) * p.n_tiles
     finally:
         asp.asp_destroy(h)
 
