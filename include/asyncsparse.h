@@ -13,7 +13,9 @@
  *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device
  *     memory of the GPU that was current when the handle was created.
  *   - A handle is immutable after creation: concurrent asp_spmm calls on
- *     different streams with different C buffers are safe.
+ *     different streams with different C buffers are safe.  The one exception
+ *     is a WCSR handle whose split windows go through the handle's scratch
+ *     buffer (asp_reserve): those calls must be ordered on one stream.
  *   - The library needs a gfx950 GPU for everything except the calls marked
  *     "host only".  There is no CPU fallback for the product.
  */
@@ -36,7 +38,7 @@ typedef enum {
     ASP_ERR_UNSUPPORTED = 3,      /* block/window size, dtype or mode not built */
     ASP_ERR_OUT_OF_MEMORY = 4,
     ASP_ERR_HIP = 5,              /* a HIP runtime call failed (no GPU, launch error, ...) */
-    ASP_ERR_BUFFER_TOO_SMALL = 6  /* asp_export: dst_bytes < *needed */
+    ASP_ERR_BUFFER_TOO_SMALL = 6  /* asp_export: dst_bytes < *needed; asp_spmm: scratch not reserved for this N */
 } asp_status_t;
 
 typedef enum { ASP_FMT_BCSR = 0, ASP_FMT_WCSR = 1 } asp_format_t;
@@ -50,7 +52,7 @@ typedef enum { ASP_DT_BF16 = 0, ASP_DT_F32 = 1 } asp_dtype_t;
 
 typedef struct {
     int32_t format;    /* asp_format_t */
-    int32_t dtype;     /* asp_dtype_t; supported pairs: BCSR+bf16, BCSR+f32, WCSR+f32 */
+    int32_t dtype;     /* asp_dtype_t; both dtypes are built for both formats */
     int32_t b_row;     /* BCSR: block height in {32,64,128}; WCSR: window height in {16,32,64} */
     int32_t b_col;     /* BCSR: block width, = b_row; WCSR: column padding unit, = 8 */
     int32_t task_cols; /* WCSR: packed columns per sub-task, positive multiple of b_col; 0 = default (512) */
@@ -113,10 +115,25 @@ asp_status_t asp_create_from_csr(const asp_config_t *cfg, int64_t m, int64_t k, 
  * N >= 1.  stream: hipStream_t (NULL = default).  Asynchronous: only enqueues kernels, never
  * synchronises, never allocates.  bf16: fp32 accumulation, round-to-nearest-even to bf16 on store.
  * f32: fp32 products and sums on the matrix cores (no reduced-precision operand formats).
- * f32 WCSR: windows that are split into several tasks are combined with fp32 atomic adds, so their
- * rows may differ in the last bits from run to run; everything else is bitwise reproducible.
+ * WCSR windows that are split into several tasks: with scratch memory (asp_reserve) the tasks' fp32 partial
+ * tiles are added in task order and rounded once; an f32 handle without scratch adds into C with fp32
+ * atomics, and only then may those rows differ in the last bits from run to run.  Everything else is
+ * bitwise reproducible.
  */
 asp_status_t asp_spmm(const asp_handle_t *h, const void *B, void *C, int64_t N, void *stream);
+
+/*
+ * Scratch memory for asp_spmm calls of width up to N (Section III-C: the partial sums of a row-window that
+ * is split into several tasks have to meet somewhere).  With scratch, every task of a split window stores
+ * its fp32 partial tile (4 * b_row * N bytes per task) and a last kernel adds the tiles in task order: the
+ * result is bitwise reproducible.  bf16 WCSR handles with split windows need it (bf16 C cannot take fp32
+ * atomic adds); f32 WCSR handles use it when it is there and otherwise add into C with fp32 atomics.  BCSR
+ * handles and WCSR handles without split windows use none: the call does nothing for them.
+ * Allocates (and frees a smaller earlier buffer, which synchronises the device); asp_spmm itself never
+ * allocates and returns ASP_ERR_BUFFER_TOO_SMALL when a bf16 call needs more scratch than was reserved.
+ * Calls on one handle that use the scratch share it and must be ordered on one stream.
+ */
+asp_status_t asp_reserve(asp_handle_t *h, int64_t N);
 
 /*
  * Y = X x A^T with K-contiguous dense operands: the same product as asp_spmm with B = X^T and C = Y^T, in

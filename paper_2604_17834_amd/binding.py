@@ -27,7 +27,7 @@ _DT = {"bf16": ASP_DT_BF16, "f32": ASP_DT_F32}
 _NP = {ASP_DT_BF16: np.uint16, ASP_DT_F32: np.float32}
 
 EXPORTED_SYMBOLS = [
-    "asp_create_from_csr", "asp_spmm", "asp_spmm_xt", "asp_get_info", "asp_plan_spmm", "asp_export", "asp_destroy",
+    "asp_create_from_csr", "asp_spmm", "asp_spmm_xt", "asp_reserve", "asp_get_info", "asp_plan_spmm", "asp_export", "asp_destroy",
     "asp_status_string", "asp_last_error",
 ]
 
@@ -79,6 +79,8 @@ def lib() -> ctypes.CDLL:
     L.asp_spmm.restype = ctypes.c_int
     L.asp_spmm_xt.argtypes = [vp, vp, vp, i64, vp]
     L.asp_spmm_xt.restype = ctypes.c_int
+    L.asp_reserve.argtypes = [vp, i64]
+    L.asp_reserve.restype = ctypes.c_int
     L.asp_get_info.argtypes = [vp, ctypes.POINTER(asp_info_t)]
     L.asp_get_info.restype = ctypes.c_int
     L.asp_plan_spmm.argtypes = [vp, i64, ctypes.POINTER(asp_plan_t)]
@@ -124,6 +126,14 @@ def asp_spmm(handle, B_ptr, C_ptr, N, stream=None, check=True):
     st = lib().asp_spmm(handle, B_ptr, C_ptr, N, stream)
     if check and st != ASP_OK:
         raise AspError(st, "asp_spmm")
+    return st
+
+
+def asp_reserve(handle, N, check=True):
+    """Scratch memory for asp_spmm calls of width up to N (only bf16 WCSR handles with split windows need any)."""
+    st = lib().asp_reserve(handle, N)
+    if check and st != ASP_OK:
+        raise AspError(st, "asp_reserve")
     return st
 
 

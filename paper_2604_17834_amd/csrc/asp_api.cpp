@@ -26,6 +26,8 @@ static void free_device(asp_handle *h) {
     (void)hipFree(h->d_tasks);
     (void)hipFree(h->d_zero_windows);
     (void)hipFree(h->d_rank_info);
+    (void)hipFree(h->d_ws_slot);
+    (void)hipFree(h->d_ws);
     if (cur >= 0 && cur != h->device) (void)hipSetDevice(cur);
 }
 
@@ -80,6 +82,16 @@ static asp_status_t create_impl(const asp_config_t *cfg, int64_t m, int64_t k, i
     h->n_units = (int64_t)h->hw.window_col_idx.size();
     wcsr_zero_windows(h->hw.window_row_ptr, h->task_cols, h->hw.zero_windows);
     h->n_zero_windows = (int64_t)h->hw.zero_windows.size();
+    {
+        const auto &wrp = h->hw.window_row_ptr;
+        h->hw.ws_slot.assign(wrp.size() - 1, -1);
+        for (size_t w = 0; w + 1 < wrp.size(); ++w)
+            if (wrp[w + 1] - wrp[w] > h->task_cols) {
+                h->hw.ws_slot[w] = (int32_t)h->n_split_tasks;
+                h->n_split_tasks += ceil_div(wrp[w + 1] - wrp[w], h->task_cols);
+                ++h->n_split_windows;
+            }
+    }
     if (host_only) {
         wcsr_tasks_host(h->hw.window_row_ptr, h->task_cols, h->hw.tasks);
         h->n_tasks = (int64_t)h->hw.tasks.size() / 4;
@@ -91,6 +103,7 @@ static asp_status_t create_impl(const asp_config_t *cfg, int64_t m, int64_t k, i
     if ((s = upload(&h->d_col_idx, h->hw.window_col_idx.data(), h->hw.window_col_idx.size() * 4, stream))) return s;
     if ((s = upload(&h->d_values, h->hw.values.data(), h->hw.values.size(), stream))) return s;
     if ((s = upload(&h->d_zero_windows, h->hw.zero_windows.data(), h->hw.zero_windows.size() * 4, stream))) return s;
+    if ((s = upload(&h->d_ws_slot, h->hw.ws_slot.data(), h->hw.ws_slot.size() * 4, stream))) return s;
     if ((s = wcsr_build_tasks_device(h, stream))) return s;  // wavefront-scan partition on the GPU
     ASP_HIP_TRY(hipStreamSynchronize(stream));
     // the device arrays are the canonical ones; drop the host copies (values can be gigabytes)
@@ -119,7 +132,7 @@ asp_status_t asp_create_from_csr(const asp_config_t *cfg, int64_t m, int64_t k, 
         if (!(cfg->b_row == 32 || cfg->b_row == 64 || cfg->b_row == 128) || cfg->b_col != cfg->b_row)
             return fail(ASP_ERR_UNSUPPORTED, "BCSR blocks must be 32x32, 64x64 or 128x128");
     } else if (cfg->format == ASP_FMT_WCSR) {
-        if (cfg->dtype != ASP_DT_F32) return fail(ASP_ERR_UNSUPPORTED, "WCSR is built for f32 only");
+        if (cfg->dtype != ASP_DT_BF16 && cfg->dtype != ASP_DT_F32) return fail(ASP_ERR_INVALID_ARG, "unknown dtype");
         if (!(cfg->b_row == 16 || cfg->b_row == 32 || cfg->b_row == 64) || cfg->b_col != 8)
             return fail(ASP_ERR_UNSUPPORTED, "WCSR needs b_row in {16,32,64} and b_col = 8");
         if (cfg->task_cols < 0 || cfg->task_cols % cfg->b_col != 0)
@@ -160,6 +173,28 @@ asp_status_t asp_spmm(const asp_handle_t *h, const void *B, void *C, int64_t N, 
     if (N >= (1ll << 31) || h->m * N >= (1ll << 40)) return fail(ASP_ERR_UNSUPPORTED, "N too large");
     if (h->format == ASP_FMT_BCSR) return bcsr_spmm_launch(h, B, C, N, (hipStream_t)stream);
     return wcsr_spmm_launch(h, B, C, N, (hipStream_t)stream);
+}
+
+asp_status_t asp_reserve(asp_handle_t *h, int64_t N) {
+    if (!h) return fail(ASP_ERR_INVALID_ARG, "null handle");
+    if (N < 1 || N >= (1ll << 31)) return fail(ASP_ERR_INVALID_ARG, "N out of range");
+    if (h->device < 0) return fail(ASP_ERR_UNSUPPORTED, "handle was converted on the host only; it has no device arrays");
+    if (h->format != ASP_FMT_WCSR || h->n_split_tasks == 0) return ASP_OK;  // uses none
+    const int64_t need = wcsr_scratch_floats(h, N);
+    if (need <= h->ws_floats) return ASP_OK;
+    int cur = -1;
+    ASP_HIP_TRY(hipGetDevice(&cur));
+    if (cur != h->device) ASP_HIP_TRY(hipSetDevice(h->device));
+    (void)hipFree(h->d_ws);  // waits for the device, so no earlier call can still be using it
+    h->d_ws = nullptr;
+    h->ws_floats = 0;
+    hipError_t e = hipMalloc((void **)&h->d_ws, (size_t)need * 4);
+    if (cur != h->device) (void)hipSetDevice(cur);
+    if (e != hipSuccess)
+        return fail(e == hipErrorOutOfMemory ? ASP_ERR_OUT_OF_MEMORY : ASP_ERR_HIP,
+                    std::string("hipMalloc of the scratch buffer: ") + hipGetErrorString(e));
+    h->ws_floats = need;
+    return ASP_OK;
 }
 
 asp_status_t asp_spmm_xt(const asp_handle_t *h, const void *X, void *Y, int64_t N, void *stream) {

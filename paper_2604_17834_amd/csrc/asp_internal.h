@@ -45,6 +45,7 @@ struct HostWcsr {
     std::vector<uint8_t> values;          // [padded_cols / b_col][b_row][b_col], raw bytes
     std::vector<int32_t> tasks;           // [n_tasks][4]; filled on the host only in host-convert mode
     std::vector<int32_t> zero_windows;    // windows whose C rows must be cleared (empty or split)
+    std::vector<int32_t> ws_slot;         // [n_windows] first scratch slot of a split window (one per task), -1 for the others
 };
 
 // converters (asp_convert.cpp); values are only bit-copied
@@ -70,6 +71,8 @@ struct asp_handle {
     uint32_t flags = 0;
     int device = -1;  // HIP device that owns the d_* arrays, -1 in host-convert mode
     int64_t n_brows = 0, n_units = 0, n_tasks = 0, n_zero_windows = 0;
+    int64_t n_split_windows = 0;  // WCSR: windows with more than one task
+    int64_t n_split_tasks = 0;    // WCSR: tasks of those windows = scratch slots
 
     asp::HostBcsr hb;  // BCSR: canonical arrays stay on the host for export
     asp::HostWcsr hw;  // WCSR: kept only in host-convert mode (device arrays are canonical)
@@ -82,6 +85,10 @@ struct asp_handle {
     int32_t *d_zero_windows = nullptr;
     int32_t *d_rank_info = nullptr; // BCSR: [n_brows][4] = {block-row, first block, stored blocks, block column of the first one}, heaviest first
     int n_cus = 0;                  // compute units of the owning device
+    // WCSR: where the tasks of split windows put their partial tiles
+    int32_t *d_ws_slot = nullptr;   // [n_windows] first scratch slot of a split window, -1 otherwise
+    float *d_ws = nullptr;          // fp32 scratch, one [b_row][N] tile per slot (asp_reserve)
+    int64_t ws_floats = 0;          // its capacity
 };
 
 namespace asp {
@@ -107,6 +114,12 @@ struct WcsrPlan {
 };
 WcsrPlan wcsr_plan(const asp_handle *h, int64_t N, bool aligned);
 asp_status_t wcsr_spmm_launch(const asp_handle *h, const void *B, void *C, int64_t N, hipStream_t stream);
+asp_status_t wcsr_bf16_spmm_launch(const asp_handle *h, const void *B, void *C, int64_t N, hipStream_t stream);
+int64_t wcsr_scratch_floats(const asp_handle *h, int64_t N);  // fp32 scratch elements a call of width N uses
+// clears the C rows of windows without columns (keep_split: and leaves split windows alone; else clears them too)
+void wcsr_clear_empty_windows(const asp_handle *h, void *C, int64_t N, bool keep_split, hipStream_t stream);
+// rows of split windows = sum of their tasks' partial tiles, in task order
+void wcsr_sum_partial_tiles(const asp_handle *h, void *C, int64_t N, hipStream_t stream);
 // GPU task partition: fills h->d_tasks / h->n_tasks from h->d_row_ptr (wavefront scans)
 asp_status_t wcsr_build_tasks_device(asp_handle *h, hipStream_t stream);
 }  // namespace asp

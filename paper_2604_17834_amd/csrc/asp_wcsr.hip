@@ -13,6 +13,7 @@
 //
 // The paper fixes the window height at 64 to fit the Hopper instruction; the CDNA fp32 MFMAs are
 // 16 or 32 rows tall, so heights 16 (default), 32 and 64 are built.
+#include <algorithm>
 #include <cstdlib>
 
 #include "asp_internal.h"
@@ -23,19 +24,60 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 // ---- zero the C rows that the main kernel will not plainly overwrite -------------------------------
-// (windows without columns, and windows split over several tasks that accumulate with atomics)
-__global__ __launch_bounds__(256) void wcsr_zero_rows_kernel(const int32_t *__restrict__ zero_windows, int b_row,
-                                                             float *__restrict__ C, int M, int64_t N, bool vec) {
+// (windows without columns; and, when they accumulate with atomics, windows split over several tasks)
+// ws_slot != nullptr: split windows (slot >= 0) are left alone, their rows come from the partial tiles.
+__global__ __launch_bounds__(256) void wcsr_zero_rows_kernel(const int32_t *__restrict__ zero_windows,
+                                                             const int32_t *__restrict__ ws_slot, int b_row,
+                                                             uint8_t *__restrict__ C, int esize, int M, int64_t N,
+                                                             bool vec) {
     const int w = zero_windows[blockIdx.x];
+    if (ws_slot && ws_slot[w] >= 0) return;
     const int64_t r0 = (int64_t)w * b_row;
     const int64_t r1 = r0 + b_row < M ? r0 + b_row : M;
-    float *base = C + r0 * N;
-    const int64_t count = (r1 - r0) * N;
-    if (vec) {
-        float4 *b4 = (float4 *)base;
-        for (int64_t i = threadIdx.x; i < count / 4; i += 256) b4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    uint8_t *base = C + r0 * N * esize;
+    const int64_t bytes = (r1 - r0) * N * esize;
+    if (vec) {  // row size and base are multiples of 16 bytes
+        uint4 *b4 = (uint4 *)base;
+        for (int64_t i = threadIdx.x; i < bytes / 16; i += 256) b4[i] = make_uint4(0, 0, 0, 0);
+    } else if (esize == 4) {
+        for (int64_t i = threadIdx.x; i < bytes / 4; i += 256) ((uint32_t *)base)[i] = 0u;
     } else {
-        for (int64_t i = threadIdx.x; i < count; i += 256) base[i] = 0.f;
+        for (int64_t i = threadIdx.x; i < bytes / 2; i += 256) ((uint16_t *)base)[i] = 0;
+    }
+}
+
+// ---- rows of split windows from the partial tiles of their tasks (Section III-C) ---------------------
+// Task j of a split window stored its fp32 partial tile [b_row][N] in slot ws_slot[w] + j of the scratch
+// buffer.  One thread per output element adds the tiles in task order (fixed order: bitwise reproducible)
+// and rounds once to the output type.
+template <typename OutT, int U>  // U = elements per thread and access: 4 (16-byte loads) or 1
+__global__ __launch_bounds__(256) void wcsr_sum_partials_kernel(const int32_t *__restrict__ zero_windows,
+                                                                const int32_t *__restrict__ ws_slot,
+                                                                const int32_t *__restrict__ window_row_ptr,
+                                                                int task_cols, int b_row, OutT *__restrict__ C,
+                                                                const float *__restrict__ ws, int M, int64_t N) {
+    typedef float vec_t __attribute__((ext_vector_type(U)));
+    typedef OutT out_t __attribute__((ext_vector_type(U)));
+    const int w = zero_windows[blockIdx.x];
+    const int slot0 = ws_slot[w];
+    if (slot0 < 0) return;  // a window without columns
+    const int parts = (window_row_ptr[w + 1] - window_row_ptr[w] + task_cols - 1) / task_cols;
+    const int64_t r0 = (int64_t)w * b_row, r1 = r0 + b_row < M ? r0 + b_row : M;
+    const int64_t units = (r1 - r0) * N / U, tile = (int64_t)b_row * N / U;
+    const vec_t *src = (const vec_t *)(ws + (int64_t)slot0 * b_row * N);
+    out_t *dst = (out_t *)(C + r0 * N);
+    for (int64_t i = (int64_t)blockIdx.y * 256 + threadIdx.x; i < units; i += (int64_t)gridDim.y * 256) {
+        vec_t sum = src[i];
+        int j = 1;
+        for (; j + 8 <= parts; j += 8) {  // 8 independent loads in flight, added in task order
+            vec_t t[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) t[e] = src[(j + e) * tile + i];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sum += t[e];
+        }
+        for (; j < parts; ++j) sum += src[j * tile + i];
+        dst[i] = __builtin_convertvector(sum, out_t);  // bf16: round to nearest even
     }
 }
 
@@ -75,6 +117,25 @@ __device__ __forceinline__ void put4(float *__restrict__ C, int64_t row, int M, 
     }
 }
 
+// Where a task's tile goes.  An unsplit window writes its rows of C.  A split window (Section III-C) either
+// adds into C with atomics (no scratch reserved) or stores its tile into its own slot of the scratch buffer:
+// slot = first slot of the window + index of the task inside the window.
+struct SplitTarget {
+    float *base;
+    int64_t row0;  // first row of the tile in base
+    int64_t rows;  // rows that exist in base from its start (bound for the row check)
+    bool atomic;
+};
+__device__ __forceinline__ SplitTarget split_target(int4 td, int b_row, float *C, int M, int64_t N, float *ws,
+                                                    const int32_t *ws_slot, const int32_t *window_row_ptr,
+                                                    int task_cols) {
+    if (td.w != 0 && ws) {
+        const int64_t slot = ws_slot[td.x] + (td.y - window_row_ptr[td.x]) / task_cols;
+        return SplitTarget{ws + slot * b_row * N, 0, b_row, false};
+    }
+    return SplitTarget{C, (int64_t)td.x * b_row, M, td.w != 0};
+}
+
 // ---- window height 16: v_mfma_f32_16x16x4_f32 ----------------------------------------------------
 // lane l: kq = l / 16 picks one of 4 packed columns of a k step, jl = l % 16 is the MFMA N index.
 // NG = 64-column groups per wave (tile width BN = 64 * NG).
@@ -83,7 +144,9 @@ __global__ __launch_bounds__(256) void wcsr16_spmm_kernel(const int4 *__restrict
                                                           const int32_t *__restrict__ window_col_idx,
                                                           const float *__restrict__ values,
                                                           const float *__restrict__ B, float *__restrict__ C, int M,
-                                                          int64_t N, int n_tiles) {
+                                                          int64_t N, int n_tiles, float *__restrict__ ws,
+                                                          const int32_t *__restrict__ ws_slot,
+                                                          const int32_t *__restrict__ window_row_ptr, int task_cols) {
     const int64_t wave_id = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int task = (int)(wave_id / n_tiles), nt = (int)(wave_id % n_tiles);
     if (task >= n_tasks) return;  // whole wave leaves together
@@ -155,13 +218,13 @@ __global__ __launch_bounds__(256) void wcsr16_spmm_kernel(const int4 *__restrict
     }
 
     // D layout: register r of lane l is row 4*(l/16) + r, MFMA column l%16 -> C column n0 + 64g + t
-    const bool split = td.w != 0;
+    const SplitTarget out = split_target(td, 16, C, M, N, ws, ws_slot, window_row_ptr, task_cols);
 #pragma unroll
     for (int g = 0; g < NG; ++g)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             float4 v = make_float4(acc[g][0][r], acc[g][1][r], acc[g][2][r], acc[g][3][r]);
-            put4(C, (int64_t)td.x * 16 + 4 * kq + r, M, N, n0 + 64 * g, v, split, VEC);
+            put4(out.base, out.row0 + 4 * kq + r, out.rows, N, n0 + 64 * g, v, out.atomic, VEC);
         }
 }
 
@@ -173,7 +236,9 @@ __global__ __launch_bounds__(256) void wcsr32_spmm_kernel(const int4 *__restrict
                                                           const int32_t *__restrict__ window_col_idx,
                                                           const float *__restrict__ values,
                                                           const float *__restrict__ B, float *__restrict__ C, int M,
-                                                          int64_t N, int n_tiles) {
+                                                          int64_t N, int n_tiles, float *__restrict__ ws,
+                                                          const int32_t *__restrict__ ws_slot,
+                                                          const int32_t *__restrict__ window_row_ptr, int task_cols) {
     constexpr int BRW = 32 * MTW;
     const int64_t wave_id = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int task = (int)(wave_id / n_tiles), nt = (int)(wave_id % n_tiles);
@@ -226,14 +291,14 @@ __global__ __launch_bounds__(256) void wcsr32_spmm_kernel(const int4 *__restrict
     }
 
     // D layout: register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, MFMA column l%32
-    const bool split = td.w != 0;
+    const SplitTarget out = split_target(td, BRW, C, M, N, ws, ws_slot, window_row_ptr, task_cols);
 #pragma unroll
     for (int i = 0; i < MTW; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             float4 v = make_float4(acc[i][0][r], acc[i][1][r], acc[i][2][r], acc[i][3][r]);
             int row = i * 32 + 8 * (r >> 2) + 4 * kq + (r & 3);
-            put4(C, (int64_t)td.x * BRW + row, M, N, n0, v, split, VEC);
+            put4(out.base, out.row0 + row, out.rows, N, n0, v, out.atomic, VEC);
         }
 }
 
@@ -368,6 +433,13 @@ asp_status_t wcsr_build_tasks_device(asp_handle *h, hipStream_t stream) {
 // ---- host side ------------------------------------------------------------------------------------
 WcsrPlan wcsr_plan(const asp_handle *h, int64_t N, bool aligned) {
     WcsrPlan p;
+    if (h->dtype == ASP_DT_BF16) {  // one wavefront per (task, 128 columns), 4 to a workgroup; element-wise path: a workgroup per (window, 64 columns)
+        p.vectorized = (aligned && N % 8 == 0) ? 1 : 0;
+        p.bn = p.vectorized ? 128 : 64;
+        p.n_tiles = (int32_t)ceil_div(N, p.bn);
+        p.workgroups = p.vectorized ? ceil_div(h->n_tasks * p.n_tiles, 4) : h->n_brows * p.n_tiles;
+        return p;
+    }
     p.vectorized = (aligned && N % 4 == 0) ? 1 : 0;
     if (h->b_row == 16) {
         // Section IV-C rule over the built wave widths: widest that divides N, else least padding
@@ -399,14 +471,45 @@ WcsrPlan wcsr_plan(const asp_handle *h, int64_t N, bool aligned) {
     return p;
 }
 
+int64_t wcsr_scratch_floats(const asp_handle *h, int64_t N) { return h->n_split_tasks * h->b_row * N; }
+
+void wcsr_clear_empty_windows(const asp_handle *h, void *C, int64_t N, bool keep_split, hipStream_t stream) {
+    if (h->n_zero_windows == 0) return;
+    const int es = (int)dtype_size(h->dtype);
+    const bool vec = ((uintptr_t)C & 15) == 0 && (N * es) % 16 == 0;
+    hipLaunchKernelGGL(wcsr_zero_rows_kernel, dim3((unsigned)h->n_zero_windows), dim3(256), 0, stream,
+                       h->d_zero_windows, keep_split ? h->d_ws_slot : nullptr, h->b_row, (uint8_t *)C, es, (int)h->m, N,
+                       vec);
+}
+
+void wcsr_sum_partial_tiles(const asp_handle *h, void *C, int64_t N, hipStream_t stream) {
+    if (h->n_split_tasks == 0) return;
+    const bool vec = N % 4 == 0 && ((uintptr_t)C & 15) == 0;
+    const unsigned gy = (unsigned)std::min<int64_t>(64, ceil_div((int64_t)h->b_row * N, vec ? 1024 : 256));
+    dim3 grid((unsigned)h->n_zero_windows, gy), block(256);
+#define ASP_SUM(T, U)                                                                                              \
+    hipLaunchKernelGGL((wcsr_sum_partials_kernel<T, U>), grid, block, 0, stream, h->d_zero_windows, h->d_ws_slot, \
+                       h->d_row_ptr, h->task_cols, h->b_row, (T *)C, h->d_ws, (int)h->m, N)
+    if (h->dtype == ASP_DT_BF16) {
+        if (vec) ASP_SUM(__bf16, 4);
+        else ASP_SUM(__bf16, 1);
+    } else {
+        if (vec) ASP_SUM(float, 4);
+        else ASP_SUM(float, 1);
+    }
+#undef ASP_SUM
+}
+
 asp_status_t wcsr_spmm_launch(const asp_handle *h, const void *B, void *C, int64_t N, hipStream_t stream) {
+    if (h->dtype == ASP_DT_BF16) return wcsr_bf16_spmm_launch(h, B, C, N, stream);
     const bool aligned = (((uintptr_t)B | (uintptr_t)C) & 15) == 0;
     const WcsrPlan p = wcsr_plan(h, N, aligned);
     const bool vec = p.vectorized != 0;
     if (p.workgroups >= (1ll << 31)) return fail(ASP_ERR_UNSUPPORTED, "too many wave tasks");
-    if (h->n_zero_windows > 0)
-        hipLaunchKernelGGL(wcsr_zero_rows_kernel, dim3((unsigned)h->n_zero_windows), dim3(256), 0, stream,
-                           h->d_zero_windows, h->b_row, (float *)C, (int)h->m, N, vec);
+    // split windows: partial tiles in the scratch buffer when it is large enough, else atomic adds into C
+    const bool partial = h->n_split_tasks > 0 && h->ws_floats >= wcsr_scratch_floats(h, N);
+    float *ws = partial ? h->d_ws : nullptr;
+    wcsr_clear_empty_windows(h, C, N, partial, stream);
     if (h->n_tasks > 0) {
         dim3 grid((unsigned)p.workgroups), block(256);
         const int4 *tasks = (const int4 *)h->d_tasks;
@@ -418,19 +521,19 @@ asp_status_t wcsr_spmm_launch(const asp_handle *h, const void *B, void *C, int64
     do {                                                                                                              \
         if (vec)                                                                                                      \
             hipLaunchKernelGGL((wcsr16_spmm_kernel<NG, true>), grid, block, 0, stream, tasks, nt, h->d_col_idx, vals, \
-                               Bf, Cf, M, N, p.n_tiles);                                                              \
+                               Bf, Cf, M, N, p.n_tiles, ws, h->d_ws_slot, h->d_row_ptr, h->task_cols);                  \
         else                                                                                                          \
             hipLaunchKernelGGL((wcsr16_spmm_kernel<NG, false>), grid, block, 0, stream, tasks, nt, h->d_col_idx,      \
-                               vals, Bf, Cf, M, N, p.n_tiles);                                                        \
+                               vals, Bf, Cf, M, N, p.n_tiles, ws, h->d_ws_slot, h->d_row_ptr, h->task_cols);          \
     } while (0)
 #define ASP_W32(MTW)                                                                                                   \
     do {                                                                                                               \
         if (vec)                                                                                                       \
             hipLaunchKernelGGL((wcsr32_spmm_kernel<MTW, true>), grid, block, 0, stream, tasks, nt, h->d_col_idx, vals, \
-                               Bf, Cf, M, N, p.n_tiles);                                                               \
+                               Bf, Cf, M, N, p.n_tiles, ws, h->d_ws_slot, h->d_row_ptr, h->task_cols); \
         else                                                                                                           \
             hipLaunchKernelGGL((wcsr32_spmm_kernel<MTW, false>), grid, block, 0, stream, tasks, nt, h->d_col_idx,      \
-                               vals, Bf, Cf, M, N, p.n_tiles);                                                         \
+                               vals, Bf, Cf, M, N, p.n_tiles, ws, h->d_ws_slot, h->d_row_ptr, h->task_cols); \
     } while (0)
         if (h->b_row == 16) {
             if (p.bn == 256) ASP_W16(4);
@@ -444,6 +547,7 @@ asp_status_t wcsr_spmm_launch(const asp_handle *h, const void *B, void *C, int64
 #undef ASP_W16
 #undef ASP_W32
     }
+    if (partial) wcsr_sum_partial_tiles(h, C, N, stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(ASP_ERR_HIP, std::string("WCSR kernel launch: ") + hipGetErrorString(e));
     return ASP_OK;

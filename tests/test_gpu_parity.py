@@ -23,7 +23,7 @@ def _dev_in(x: np.ndarray):
     return torch.from_numpy(x).cuda()
 
 
-def gpu_spmm(a: synth.Csr, fmt, b_row, b_col, B: np.ndarray, task_cols=0, handle=None, misalign=False):
+def gpu_spmm(a: synth.Csr, fmt, b_row, b_col, B: np.ndarray, task_cols=0, handle=None, misalign=False, reserve=True):
     """One asp_create_from_csr + asp_spmm; returns C as numpy (uint16 bits or float32)."""
     own = handle is None
     if own:
@@ -47,6 +47,8 @@ def gpu_spmm(a: synth.Csr, fmt, b_row, b_col, B: np.ndarray, task_cols=0, handle
         else:
             Cd.fill_(float("nan"))
         stream = torch.cuda.current_stream().cuda_stream
+        if reserve:   # scratch for the partial tiles of split WCSR windows; nothing for other handles
+            asp.asp_reserve(handle, N)
         asp.asp_spmm(handle, Bd.data_ptr(), Cd.data_ptr(), N, stream)
         torch.cuda.synchronize()
         out = Cd.cpu().numpy()
@@ -358,6 +360,34 @@ def test_wcsr_unsplit_is_bitwise_reproducible_and_slice_consistent():
         asp.asp_destroy(h)
 
 
+@pytest.mark.parametrize("b_row,N", [(16, 128), (32, 100), (64, 50)])
+def test_wcsr_f32_split_windows_without_scratch_use_atomics(b_row, N):
+    # no asp_reserve: the tasks of a split window add into cleared rows of C with fp32 atomics
+    a = synth.random_csr(200, 512, 0.10, seed=300 + b_row, dtype="f32", empty_row_frac=0.1)
+    B = synth.dense_normal(a.k, N, "f32", seed=31)
+    check_against_oracle(a, B, gpu_spmm(a, "wcsr", b_row, 8, B, task_cols=16, reserve=False))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_wcsr_split_windows_with_scratch_are_bitwise_reproducible(dtype):
+    # partial tiles are added in task order: two runs give the same bits, and so does a wider reservation
+    a = synth.zipf_graph(2048, 2048, 16 * 2048, seed=11, cap=900, dtype=dtype)
+    B = synth.dense_normal(a.k, 128, dtype, seed=12)
+    h = asp.asp_create_from_csr("wcsr", dtype, 16, 8, a.m, a.k, a.row_ptr, a.col_idx, a.values, task_cols=64)
+    try:
+        tasks = asp.asp_export(h, asp.ASP_ARR_TASKS)
+        assert tasks[:, 3].any()
+        C1 = gpu_spmm(a, "wcsr", 16, 8, B, handle=h)
+        C2 = gpu_spmm(a, "wcsr", 16, 8, B, handle=h)
+        assert np.array_equal(C1.view(np.uint8), C2.view(np.uint8))
+        asp.asp_reserve(h, 512)
+        C3 = gpu_spmm(a, "wcsr", 16, 8, B, handle=h)
+        assert np.array_equal(C1.view(np.uint8), C3.view(np.uint8))
+        check_against_oracle(a, B, C1)
+    finally:
+        asp.asp_destroy(h)
+
+
 def test_wcsr_task_cols_does_not_change_result_beyond_tolerance():
     a = synth.zipf_graph(2048, 2048, 16 * 2048, seed=11, cap=900)
     B = synth.dense_normal(a.k, 128, "f32", seed=12)
@@ -456,3 +486,111 @@ def test_bcsr_f32_geometric_rows_sampled_and_rerun_bitwise():
     finally:
         asp.asp_destroy(h)
     check_against_oracle(a, B, C1, _sample_columns(1024, 256, np.random.default_rng(3)))
+
+
+# ------------------------------------------------------------------ WCSR in bf16 (both formats at one precision)
+@pytest.mark.parametrize("b_row", [16, 32, 64])
+@pytest.mark.parametrize("m,k,N,density,task_cols", [
+    (256, 300, 128, 0.05, 0),      # one 128-column tile, no splits
+    (200, 512, 64, 0.10, 16),      # N below the tile width; splits: fp32 scratch + final rounding
+    (333, 257, 256, 0.03, 8),      # ragged last window, every window split, two tiles
+    (128, 128, 200, 0.10, 32),     # masked N tail on the 16-byte path (200 % 8 == 0)
+    (300, 700, 384, 0.20, 64),     # long windows: many stages per task, several tasks per window
+    (77, 140, 50, 0.15, 24),       # N % 8 != 0: element-wise path
+    (64, 64, 8, 0.2, 0),
+    (64, 64, 1, 0.2, 8),
+])
+def test_wcsr_bf16_parity(b_row, m, k, N, density, task_cols):
+    a = synth.random_csr(m, k, density, seed=400 + m + N, dtype="bf16", empty_row_frac=0.15)
+    B = synth.dense_normal(k, N, "bf16", seed=19 + N)
+    C = gpu_spmm(a, "wcsr", b_row, 8, B, task_cols=task_cols)
+    check_against_oracle(a, B, C)
+    assert not C[np.diff(a.row_ptr) == 0].any()
+
+
+@pytest.mark.parametrize("b_row,task_cols", [(16, 16), (32, 1 << 20), (64, 40)])
+def test_wcsr_bf16_times_identity_is_A_bit_exact(b_row, task_cols):
+    # exact products and sums, and one rounding of an exactly representable value: split or not, A's bits come back
+    a = synth.random_csr(150, 128, 0.08, seed=60 + b_row, dtype="bf16")
+    C = gpu_spmm(a, "wcsr", b_row, 8, synth.dense_identity(a.k, "bf16"), task_cols=task_cols)
+    dense = np.zeros((a.m, a.k), np.uint16)
+    for i in range(a.m):
+        dense[i, a.col_idx[a.row_ptr[i]:a.row_ptr[i + 1]]] = a.values[a.row_ptr[i]:a.row_ptr[i + 1]]
+    dense[dense == 0x8000] = 0   # a stored -0.0 adds up to +0.0
+    assert np.array_equal(C, dense)
+
+
+def test_wcsr_bf16_pads_and_edges_never_read_B():
+    # NaN rows of B that no stored column addresses, and a NaN-poisoned neighbourhood of the tile edge, must not leak:
+    # pads and the columns past N load constants, not data
+    a = synth.random_csr(96, 64, 0.12, seed=71, dtype="bf16")
+    used = np.zeros(a.k, bool)
+    used[a.col_idx] = True
+    B = synth.dense_normal(a.k, 72, "bf16", seed=72)
+    B[~used] = 0x7FC0
+    C = gpu_spmm(a, "wcsr", 16, 8, B)
+    B0 = B.copy()
+    B0[~used] = 0
+    check_against_oracle(a, B0, C)
+
+
+def test_wcsr_bf16_unsplit_bitwise_reproducible_slices_and_misalignment():
+    a = synth.zipf_graph(4096, 4096, 16 * 4096, seed=8, cap=400, dtype="bf16")
+    B = synth.dense_normal(a.k, 256, "bf16", seed=9)
+    h = asp.asp_create_from_csr("wcsr", "bf16", 16, 8, a.m, a.k, a.row_ptr, a.col_idx, a.values, task_cols=1 << 20)
+    try:
+        C1 = gpu_spmm(a, "wcsr", 16, 8, B, handle=h)
+        assert np.array_equal(C1, gpu_spmm(a, "wcsr", 16, 8, B, handle=h))
+        Cs = gpu_spmm(a, "wcsr", 16, 8, np.ascontiguousarray(B[:, 64:192]), handle=h)
+        assert np.array_equal(C1[:, 64:192], Cs)
+        # the element-wise path sums in a different order: same values within the tolerance
+        check_against_oracle(a, B, gpu_spmm(a, "wcsr", 16, 8, B, handle=h, misalign=True))
+        check_against_oracle(a, B, C1)
+    finally:
+        asp.asp_destroy(h)
+
+
+def test_wcsr_bf16_scratch_must_be_reserved():
+    a = synth.random_csr(64, 256, 0.5, seed=5, dtype="bf16")
+    h = asp.asp_create_from_csr("wcsr", "bf16", 16, 8, a.m, a.k, a.row_ptr, a.col_idx, a.values, task_cols=32)
+    try:
+        B = torch.zeros((a.k, 128), dtype=torch.int16, device="cuda")
+        C = torch.zeros((a.m, 128), dtype=torch.int16, device="cuda")
+        assert asp.asp_spmm(h, B.data_ptr(), C.data_ptr(), 128, None, check=False) == asp.ASP_ERR_BUFFER_TOO_SMALL
+        assert "asp_reserve" in asp.asp_last_error()
+        asp.asp_reserve(h, 64)
+        assert asp.asp_spmm(h, B.data_ptr(), C.data_ptr(), 128, None, check=False) == asp.ASP_ERR_BUFFER_TOO_SMALL
+        assert asp.asp_spmm(h, B.data_ptr(), C.data_ptr(), 64, None) == asp.ASP_OK     # smaller width fits
+        asp.asp_reserve(h, 128)
+        assert asp.asp_spmm(h, B.data_ptr(), C.data_ptr(), 128, None) == asp.ASP_OK
+        torch.cuda.synchronize()
+    finally:
+        asp.asp_destroy(h)
+
+
+def test_wcsr_bf16_device_arrays_and_tasks_bit_exact():
+    a = synth.zipf_graph(20000, 20000, 12 * 20000, seed=13, cap=5000, dtype="bf16")
+    h = asp.asp_create_from_csr("wcsr", "bf16", 16, 8, a.m, a.k, a.row_ptr, a.col_idx, a.values, task_cols=64)
+    try:
+        wrp, wci, vals = oracle.to_wcsr(a.m, a.k, a.row_ptr, a.col_idx, a.values, "bf16", 16, 8)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_ROW_PTR), wrp)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_COL_IDX), wci)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_VALUES).ravel(), vals.ravel())
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_TASKS), oracle.wcsr_tasks(wrp, 64))
+    finally:
+        asp.asp_destroy(h)
+
+
+def test_wcsr_bf16_config3_full_size():
+    a, fmt, br, bc, N, dt, seedB = synth.workload("wcsr_zipf_bf16")
+    B = synth.dense_normal(a.k, N, dt, seedB)
+    C = gpu_spmm(a, fmt, br, bc, B)
+    check_against_oracle(a, B, C)
+
+
+def test_wcsr_bf16_config4_reduced_band_plus_dense_rows():
+    a, fmt, br, bc, _, dt, seedB = synth.workload("wcsr_band_dense_rows_bf16", scale=0.125)
+    for N in (64, 256):
+        B = synth.dense_normal(a.k, N, dt, seedB + N)
+        C = gpu_spmm(a, fmt, br, bc, B)
+        check_against_oracle(a, B, C, None if N == 64 else np.arange(96, 160))

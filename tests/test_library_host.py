@@ -158,6 +158,32 @@ def test_wcsr_converter_and_tasks_bit_exact_vs_oracle(m, k, br, density, task_co
         asp.asp_destroy(h)
 
 
+@pytest.mark.parametrize("br,task_cols", [(16, 16), (32, 0), (64, 24)])
+def test_wcsr_bf16_converter_tasks_and_plan(br, task_cols):
+    a = synth.random_csr(200, 257, 0.08, 8, "bf16", empty_row_frac=0.2)
+    h = asp.asp_create_from_csr("wcsr", "bf16", br, 8, a.m, a.k, a.row_ptr, a.col_idx, a.values, task_cols=task_cols,
+                                flags=HOST)
+    try:
+        wrp, wci, vals = oracle.to_wcsr(a.m, a.k, a.row_ptr, a.col_idx, a.values, "bf16", br, 8)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_ROW_PTR), wrp)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_COL_IDX), wci)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_VALUES).ravel(), vals.ravel())
+        tasks = oracle.wcsr_tasks(wrp, task_cols or 512)
+        assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_TASKS), tasks)
+        for N in (128, 256, 200, 64, 8, 100, 1):   # one wave per (task, 128 columns), 4 waves to a workgroup
+            p = asp.asp_plan_spmm(h, N)
+            if N % 8 == 0:
+                assert (p.vectorized, p.bn, p.n_tiles) == (1, 128, -(-N // 128))
+                assert p.workgroups == -(-len(tasks) * p.n_tiles // 4)
+            else:                                   # element-wise path: a workgroup per (window, 64 columns)
+                assert (p.vectorized, p.bn, p.n_tiles) == (0, 64, -(-N // 64))
+                assert p.workgroups == (len(wrp) - 1) * p.n_tiles
+        assert asp.asp_reserve(h, 128, check=False) == asp.ASP_ERR_UNSUPPORTED   # no device arrays
+    finally:
+        asp.asp_destroy(h)
+    assert asp.asp_reserve(None, 128, check=False) == asp.ASP_ERR_INVALID_ARG
+
+
 def test_wcsr_converter_irregular_workloads():
     for a in (synth.zipf_graph(2048, 2048, 16 * 2048, seed=3, cap=700),
               synth.banded_plus_dense_rows(4096, seed=4, n_dense_rows=4, dense_row_nnz=1500)):
