@@ -50,7 +50,16 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
     t0 = time.time()
     # "<workload>_xt": the same matrix through the K-contiguous entry, Y[N x m] = X[N x k] x A^T
     xt = name.endswith("_xt")
-    a, fmt, b_row, b_col, N, dt, seedB = synth.workload(name[:-3] if xt else name)
+    # "<workload>_rcm": the matrix goes through the library's Reverse Cuthill-McKee reordering first (Section IV-A)
+    rcm = name.endswith("_rcm")
+    a, fmt, b_row, b_col, N, dt, seedB = synth.workload(name[:-3] if xt else name[:-4] if rcm else name)
+    t_reorder = None
+    if rcm:
+        t1 = time.time()
+        perm = asp.asp_rcm(a.m, a.row_ptr, a.col_idx)
+        rp, ci, va = asp.asp_permute_csr(a.m, a.k, a.row_ptr, a.col_idx, a.values, dt, perm, perm)
+        a = synth.Csr(a.m, a.k, rp, ci, va, dt)
+        t_reorder = time.time() - t1
     B = synth.dense_normal(N, a.k, dt, seedB) if xt else synth.dense_normal(a.k, N, dt, seedB)
     t_gen = time.time() - t0
     spmm = asp.asp_spmm_xt if xt else asp.asp_spmm
@@ -127,6 +136,8 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
         "value": flops_eff / (wall_ms * 1e-3) / 1e9, "ms_per_step": wall_ms, "roofline": roof,
         "convert_s": t_convert, "generate_s": t_gen, **extra,
     }
+    if t_reorder is not None:
+        res["reorder_s"] = t_reorder
 
     if with_cpu_baseline:
         import oracle

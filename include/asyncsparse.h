@@ -164,6 +164,41 @@ asp_status_t asp_export(const asp_handle_t *h, asp_array_t which, void *host_dst
 /* Frees host and device memory of the handle.  NULL is allowed. */
 asp_status_t asp_destroy(asp_handle_t *h);
 
+/*
+ * ---- host only: the preprocessing of the sparse-matrix evaluation (Section IV-A, "Baselines and datasets") ----
+ *
+ * Reverse Cuthill-McKee ordering of a square m x m matrix given as CSR structure (HOST arrays, valid sorted
+ * CSR as for asp_create_from_csr).  The structure is taken as that of A + A^T.  perm (HOST, m entries,
+ * written) receives perm[new] = old.  Every connected component is numbered breadth-first from its node of
+ * least degree, neighbours in order of degree (ties: lower index), and the numbering is reversed.
+ */
+asp_status_t asp_rcm(int64_t m, const int32_t *row_ptr, const int32_t *col_idx, int32_t *perm);
+
+/*
+ * A'[i][j] = A[row_perm[i]][col_perm[j]] as sorted CSR (col_perm NULL keeps the columns; the symmetric
+ * reordering of Section IV-A passes the same permutation twice).  All arrays HOST; dtype is an asp_dtype_t,
+ * values are bit-copied.  Outputs are caller-allocated: out_row_ptr m + 1 entries, out_col_idx and out_values
+ * nnz entries; they must not alias the inputs.  Permutations that are not permutations are rejected.
+ */
+asp_status_t asp_permute_csr(int64_t m, int64_t k, const int32_t *row_ptr, const int32_t *col_idx, const void *values,
+                             int32_t dtype, const int32_t *row_perm, const int32_t *col_perm, int32_t *out_row_ptr,
+                             int32_t *out_col_idx, void *out_values);
+
+/*
+ * Read a Matrix Market coordinate file (the format of the collection the paper evaluates on) into sorted CSR
+ * with float values: fields real / integer / pattern (value 1), symmetries general / symmetric /
+ * skew-symmetric (off-diagonal entries are mirrored); entries at equal positions are summed in fp64, explicit
+ * zeros stay stored.  Array files, complex and hermitian matrices return ASP_ERR_UNSUPPORTED, malformed files
+ * ASP_ERR_INVALID_CSR, a file that cannot be opened ASP_ERR_INVALID_ARG.  *out is owned by the library until
+ * asp_mtx_free; asp_mtx_get hands out its sizes and HOST array pointers (any out-pointer may be NULL), valid
+ * until the free.
+ */
+typedef struct asp_mtx asp_mtx_t;
+asp_status_t asp_mtx_read(const char *path, asp_mtx_t **out);
+asp_status_t asp_mtx_get(const asp_mtx_t *mx, int64_t *m, int64_t *k, int64_t *nnz, const int32_t **row_ptr,
+                         const int32_t **col_idx, const float **values);
+asp_status_t asp_mtx_free(asp_mtx_t *mx);
+
 /* host only */
 const char *asp_status_string(asp_status_t s);
 const char *asp_last_error(void);

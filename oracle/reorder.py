@@ -36,6 +36,15 @@ def sym_adjacency(m, row_ptr, col_idx):
     return s.indptr.astype(np.int64), s.indices.astype(np.int64)
 
 
+def degrees(m, row_ptr, col_idx) -> np.ndarray:
+    """The key by which Cuthill-McKee orders nodes: neighbours in A + A^T, a stored diagonal entry counting twice
+    (scipy's convention: the self-loop is a neighbour and is then counted once more)."""
+    indptr, indices = sym_adjacency(m, row_ptr, col_idx)
+    deg = np.diff(indptr)
+    rows = np.repeat(np.arange(m, dtype=np.int64), deg)
+    return deg + np.bincount(rows[indices == rows], minlength=m)
+
+
 def bandwidth(m, row_ptr, col_idx) -> int:
     """max |i - j| over stored entries (0 for an empty matrix)."""
     rp = np.asarray(row_ptr, dtype=np.int64)

@@ -27,7 +27,8 @@ _DT = {"bf16": ASP_DT_BF16, "f32": ASP_DT_F32}
 _NP = {ASP_DT_BF16: np.uint16, ASP_DT_F32: np.float32}
 
 EXPORTED_SYMBOLS = [
-    "asp_create_from_csr", "asp_spmm", "asp_spmm_xt", "asp_reserve", "asp_get_info", "asp_plan_spmm", "asp_export", "asp_destroy",
+    "asp_create_from_csr", "asp_spmm", "asp_spmm_xt", "asp_reserve", "asp_rcm", "asp_permute_csr",
+    "asp_mtx_read", "asp_mtx_get", "asp_mtx_free", "asp_get_info", "asp_plan_spmm", "asp_export", "asp_destroy",
     "asp_status_string", "asp_last_error",
 ]
 
@@ -81,6 +82,16 @@ def lib() -> ctypes.CDLL:
     L.asp_spmm_xt.restype = ctypes.c_int
     L.asp_reserve.argtypes = [vp, i64]
     L.asp_reserve.restype = ctypes.c_int
+    L.asp_rcm.argtypes = [i64, vp, vp, vp]
+    L.asp_rcm.restype = ctypes.c_int
+    L.asp_permute_csr.argtypes = [i64, i64, vp, vp, vp, ctypes.c_int32, vp, vp, vp, vp, vp]
+    L.asp_permute_csr.restype = ctypes.c_int
+    L.asp_mtx_read.argtypes = [ctypes.c_char_p, ctypes.POINTER(vp)]
+    L.asp_mtx_read.restype = ctypes.c_int
+    L.asp_mtx_get.argtypes = [vp] + [ctypes.POINTER(i64)] * 3 + [ctypes.POINTER(vp)] * 3
+    L.asp_mtx_get.restype = ctypes.c_int
+    L.asp_mtx_free.argtypes = [vp]
+    L.asp_mtx_free.restype = ctypes.c_int
     L.asp_get_info.argtypes = [vp, ctypes.POINTER(asp_info_t)]
     L.asp_get_info.restype = ctypes.c_int
     L.asp_plan_spmm.argtypes = [vp, i64, ctypes.POINTER(asp_plan_t)]
@@ -135,6 +146,63 @@ def asp_reserve(handle, N, check=True):
     if check and st != ASP_OK:
         raise AspError(st, "asp_reserve")
     return st
+
+
+def asp_rcm(m, row_ptr, col_idx) -> np.ndarray:
+    """Reverse Cuthill-McKee permutation (perm[new] = old) of a square CSR structure; host only."""
+    rp = np.ascontiguousarray(row_ptr, dtype=np.int32)
+    ci = np.ascontiguousarray(col_idx, dtype=np.int32)
+    perm = np.empty(m, dtype=np.int32)
+    st = lib().asp_rcm(m, rp.ctypes.data, ci.ctypes.data if len(ci) else None, perm.ctypes.data)
+    if st != ASP_OK:
+        raise AspError(st, "asp_rcm")
+    return perm
+
+
+def asp_permute_csr(m, k, row_ptr, col_idx, values, dtype, row_perm, col_perm=None, check=True):
+    """A'[i][j] = A[row_perm[i]][col_perm[j]]; returns (row_ptr, col_idx, values) or the status when check is False."""
+    dt = _DT.get(dtype, dtype)
+    rp = np.ascontiguousarray(row_ptr, dtype=np.int32)
+    ci = np.ascontiguousarray(col_idx, dtype=np.int32)
+    va = np.ascontiguousarray(values, dtype=_NP[dt])
+    rperm = np.ascontiguousarray(row_perm, dtype=np.int32)
+    cperm = None if col_perm is None else np.ascontiguousarray(col_perm, dtype=np.int32)
+    orp, oci, ova = np.empty(m + 1, np.int32), np.empty(len(ci), np.int32), np.empty(len(va), _NP[dt])
+    st = lib().asp_permute_csr(m, k, rp.ctypes.data, ci.ctypes.data if len(ci) else None,
+                               va.ctypes.data if len(va) else None, dt, rperm.ctypes.data,
+                               None if cperm is None else cperm.ctypes.data, orp.ctypes.data,
+                               oci.ctypes.data if len(oci) else None, ova.ctypes.data if len(ova) else None)
+    if st != ASP_OK:
+        if check:
+            raise AspError(st, "asp_permute_csr")
+        return st
+    return orp, oci, ova
+
+
+def asp_mtx_read(path, check=True):
+    """Matrix Market coordinate file -> (m, k, row_ptr, col_idx, values float32) as numpy copies; host only."""
+    h = ctypes.c_void_p()
+    st = lib().asp_mtx_read(os.fsencode(path), ctypes.byref(h))
+    if st != ASP_OK:
+        if check:
+            raise AspError(st, "asp_mtx_read")
+        return st
+    try:
+        m, k, nnz = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+        prp, pci, pva = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
+        st = lib().asp_mtx_get(h, ctypes.byref(m), ctypes.byref(k), ctypes.byref(nnz), ctypes.byref(prp),
+                               ctypes.byref(pci), ctypes.byref(pva))
+        if st != ASP_OK:
+            raise AspError(st, "asp_mtx_get")
+
+        def copy(ptr, n, ct, dt):
+            if n == 0:
+                return np.zeros(0, dt)
+            return np.ctypeslib.as_array(ctypes.cast(ptr, ctypes.POINTER(ct)), shape=(n,)).astype(dt, copy=True)
+        return (m.value, k.value, copy(prp, m.value + 1, ctypes.c_int32, np.int32),
+                copy(pci, nnz.value, ctypes.c_int32, np.int32), copy(pva, nnz.value, ctypes.c_float, np.float32))
+    finally:
+        lib().asp_mtx_free(h)
 
 
 def asp_spmm_xt(handle, X_ptr, Y_ptr, N, stream=None, check=True):

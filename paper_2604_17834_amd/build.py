@@ -16,7 +16,7 @@ OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libasyncsparse.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
-SOURCES = ["asp_api.cpp", "asp_convert.cpp", "asp_bcsr.hip", "asp_bcsr_dma.hip", "asp_bcsr_wide.hip", "asp_bcsr_f32.hip", "asp_wcsr.hip", "asp_wcsr_bf16.hip"]
+SOURCES = ["asp_api.cpp", "asp_convert.cpp", "asp_reorder.cpp", "asp_bcsr.hip", "asp_bcsr_dma.hip", "asp_bcsr_wide.hip", "asp_bcsr_f32.hip", "asp_wcsr.hip", "asp_wcsr_bf16.hip"]
 EXTRA = os.environ.get("ASP_EXTRA_FLAGS", "").split()
 COMMON = EXTRA + ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-result"]
 # gfx950 only; packed-fp32 VALU forms are switched off for device code

@@ -214,6 +214,21 @@ def banded_plus_dense_rows(m: int, seed: int, half_band: int = 13, n_dense_rows:
     return _csr_from_keys(m, k, keys, lambda n: rng.uniform(-1.0, 1.0, n).astype(np.float32), dtype)
 
 
+def scrambled_band(m: int, seed: int, half_band: int = 13, dtype: str = F32) -> Csr:
+    """A (2*half_band+1)-diagonal band whose rows and columns went through one random permutation: the
+    structure a bandwidth-reducing reordering can restore (stand-in for a mesh matrix in arbitrary node order)."""
+    rng = np.random.default_rng(seed)
+    p = rng.permutation(m).astype(np.int64)
+    i = np.arange(m, dtype=np.int64)
+    parts = []
+    for d in range(-half_band, half_band + 1):
+        j = i + d
+        ok = (j >= 0) & (j < m)
+        parts.append(p[i[ok]] * m + p[j[ok]])
+    keys = np.unique(np.concatenate(parts))
+    return _csr_from_keys(m, m, keys, lambda n: rng.uniform(-1.0, 1.0, n).astype(np.float32), dtype)
+
+
 # --------------------------------------------------------------------------
 # named workloads (BASELINE configs).  `scale` < 1 shrinks them for tests.
 # --------------------------------------------------------------------------
@@ -245,4 +260,8 @@ def workload(name: str, scale: float = 1.0):
         m = max(4096, int(2_000_000 * s))
         a = banded_plus_dense_rows(m, seed=1004, dense_row_nnz=max(64, int(200000 * s)), dtype=dt or F32)
         return a, "wcsr", 16, 8, 64, dt or F32, 1007
+    if name == "wcsr_scrambled_band":   # reordering study (Section IV-A): bench.py's suffix _rcm reorders it first
+        m = max(4096, int((1 << 20) * s))
+        a = scrambled_band(m, seed=1021, dtype=dt or F32)
+        return a, "wcsr", 16, 8, 128, dt or F32, 1022
     raise KeyError(name)

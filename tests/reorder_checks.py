@@ -8,12 +8,13 @@ order of non-decreasing degree.
 import numpy as np
 
 
-def assert_valid_rcm(m, indptr, indices, perm):
-    """indptr/indices: neighbour lists of the structure of A + A^T; perm[new] = old."""
+def assert_valid_rcm(m, indptr, indices, perm, deg=None):
+    """indptr/indices: neighbour lists of the structure of A + A^T; perm[new] = old; deg: the ordering key of
+    every node (default: its number of neighbours)."""
     perm = np.asarray(perm, dtype=np.int64)
     assert perm.shape == (m,) and np.array_equal(np.sort(perm), np.arange(m)), "not a permutation"
     order = perm[::-1]
-    deg = np.diff(indptr)
+    deg = np.diff(indptr) if deg is None else np.asarray(deg)
     visited = np.zeros(m, bool)
     pos = 0
     for i in range(m):

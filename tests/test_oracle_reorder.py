@@ -70,7 +70,7 @@ def test_rcm_uses_the_structure_of_a_plus_a_transpose_and_keeps_components_toget
     rp, ci = _csr_from_edges(m, edges, symmetric=False, diagonal=True)
     perm = reorder.rcm(m, rp, ci)
     indptr, indices = reorder.sym_adjacency(m, rp, ci)
-    assert_valid_rcm(m, indptr, indices, perm)
+    assert_valid_rcm(m, indptr, indices, perm, reorder.degrees(m, rp, ci))
     comp = {0: 0, 3: 0, 7: 0, 9: 0, 1: 1, 2: 1, 5: 1, 8: 1, 10: 1, 4: 2, 6: 3}
     labels = [comp[int(v)] for v in perm]
     assert sum(labels[i] != labels[i + 1] for i in range(m - 1)) == 3          # four contiguous runs
@@ -86,6 +86,19 @@ def test_rcm_on_random_banded_structure_recovers_a_narrow_band():
     perm = reorder.rcm(m, rp, ci)
     assert _bandwidth_after(m, rp, ci, perm) <= 3 * hb
     assert_valid_rcm(m, *reorder.sym_adjacency(m, rp, ci), perm)
+
+
+def test_degree_key_counts_a_stored_diagonal_twice():
+    # nodes 0-1-2 in a path, node 1 with a diagonal entry; node 3 alone with a diagonal entry; node 4 alone
+    rp, ci = _csr_from_edges(5, [(0, 1), (1, 2), (1, 1), (3, 3)])
+    assert reorder.degrees(5, rp, ci).tolist() == [1, 4, 1, 2, 0]
+    # the key decides the order: mixed diagonals, random structure -- scipy's order is valid under this key
+    rng = np.random.default_rng(9)
+    m = 200
+    edges = [(int(i), int(j)) for i, j in rng.integers(0, m, size=(500, 2))]
+    rp, ci = _csr_from_edges(m, edges)
+    assert 0 < np.count_nonzero(np.diff(rp) != reorder.degrees(m, rp, ci)) < m
+    assert_valid_rcm(m, *reorder.sym_adjacency(m, rp, ci), reorder.rcm(m, rp, ci), reorder.degrees(m, rp, ci))
 
 
 def test_permute_csr_matches_dense_indexing():
