@@ -618,3 +618,29 @@ def test_rcm_reordered_matrix_gives_the_permuted_product(fmt, b_row, b_col, dtyp
     finally:
         asp.asp_destroy(h0)
         asp.asp_destroy(h1)
+
+
+def test_sparse_linear_layers_chain_without_transposes():
+    # gate -> down of a small feed-forward block through the nn.Linear-shaped wrapper: every stage against the
+    # oracle on the bf16 activations the previous stage produced
+    from paper_2604_17834_amd.linear import SparseLinear
+    N, hid, ffn = 512, 256, 1024
+    wg = synth.block_sparse_bernoulli(ffn, hid, 128, 128, 0.5, seed=81, std=0.05)
+    wd = synth.block_sparse_bernoulli(hid, ffn, 128, 128, 0.5, seed=82, std=0.05)
+    gate = SparseLinear(ffn, hid, wg.row_ptr, wg.col_idx, wg.values)
+    down = SparseLinear(hid, ffn, wd.row_ptr, wd.col_idx, wd.values)
+    try:
+        X = synth.dense_normal(N, hid, "bf16", seed=83)
+        Xd = _dev_in(X)
+        G = torch.full((N, ffn), 0x7FC1, dtype=torch.int16, device="cuda")
+        Y = torch.full((N, hid), 0x7FC1, dtype=torch.int16, device="cuda")
+        down(gate(Xd, G), Y)
+        torch.cuda.synchronize()
+        Gh, Yh = G.cpu().numpy().view(np.uint16), Y.cpu().numpy().view(np.uint16)
+        check_against_oracle(wg, np.ascontiguousarray(X.T), np.ascontiguousarray(Gh.T))
+        check_against_oracle(wd, np.ascontiguousarray(Gh.T), np.ascontiguousarray(Yh.T))
+        with pytest.raises(ValueError):
+            gate(Xd, Y)
+    finally:
+        gate.close()
+        down.close()
