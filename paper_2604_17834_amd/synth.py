@@ -243,15 +243,19 @@ def workload(name: str, scale: float = 1.0):
     for suffix, d in (("_f32", F32), ("_bf16", BF16)):
         if name.endswith(suffix):
             name, dt = name[:-len(suffix)], d
+    blk = 128   # "_b64" / "_b32": the config-2 shapes pruned in smaller square blocks (same sparsity, own mask)
+    for suffix, b in (("_b64", 64), ("_b32", 32)):
+        if name.endswith(suffix) and name.startswith("bcsr_") and name != "bcsr_small" + suffix:
+            name, blk = name[:-len(suffix)], b
     if name == "bcsr_small":            # config 1
         a = block_sparse_bernoulli(1024, 1024, 64, 64, 0.90, seed=1001, dtype=dt or BF16)
         return a, "bcsr", 64, 64, 256, dt or BF16, 1004
     if name == "bcsr_gate_proj":        # config 2 (gate/up projection)
-        a = block_sparse_bernoulli(18944, 3584, 128, 128, 0.90, seed=1002, dtype=dt or BF16)
-        return a, "bcsr", 128, 128, max(256, int(16384 * s)), dt or BF16, 1005
+        a = block_sparse_bernoulli(18944, 3584, blk, blk, 0.90, seed=1002, dtype=dt or BF16)
+        return a, "bcsr", blk, blk, max(256, int(16384 * s)), dt or BF16, 1005
     if name == "bcsr_down_proj":        # config 2 (down projection)
-        a = block_sparse_bernoulli(3584, 18944, 128, 128, 0.90, seed=1012, dtype=dt or BF16)
-        return a, "bcsr", 128, 128, max(256, int(16384 * s)), dt or BF16, 1015
+        a = block_sparse_bernoulli(3584, 18944, blk, blk, 0.90, seed=1012, dtype=dt or BF16)
+        return a, "bcsr", blk, blk, max(256, int(16384 * s)), dt or BF16, 1015
     if name == "wcsr_zipf":             # config 3
         m = max(1024, int((1 << 20) * s))
         a = zipf_graph(m, m, 16 * m, seed=1003, dtype=dt or F32)
