@@ -70,10 +70,9 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
     t_convert = time.time() - t0
     info = asp.asp_get_info(h)
     plan = asp.asp_plan_spmm(h, N)
-    if dt == "bf16":
-        # scratch for the partial tiles of split WCSR windows (set-up, like the conversion).  fp32 WCSR handles run
-        # without it (atomic adds into C: ~2 % faster on this workload, not bitwise reproducible); no-op for BCSR
-        asp.asp_reserve(h, N)
+    # scratch for the partial tiles of split WCSR windows (set-up, like the conversion): bf16 handles need it, fp32
+    # handles run at the same speed with it and are bitwise reproducible; nothing is allocated for other handles
+    asp.asp_reserve(h, N)
 
     if dt == "bf16":
         Bd = torch.from_numpy(B.view(np.int16)).cuda()
@@ -116,11 +115,10 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
         real_cols = int((wci >= 0).sum())
         split_windows = int(len(np.unique(tasks[tasks[:, 3] != 0, 0]))) if len(tasks) else 0
         # per packed column: b_row values + 1 index of A, one gathered B row; per window one C tile
-        # (split windows, fp32: cleared, then read-modify-written by every task -- counted as 2 extra passes over
-        # their rows; bf16: every task of a split window writes a fp32 partial tile that is read back once)
+        # (every task of a split window writes a fp32 partial tile that is read back once)
         split_tasks = int((tasks[:, 3] != 0).sum()) if len(tasks) else 0
         bytes_alg = (info.n_units * (b_row * esz + 4) + real_cols * N * esz + a.m * N * esz
-                     + 2 * (split_windows if dt == "f32" else split_tasks) * b_row * N * 4)
+                     + 2 * split_tasks * b_row * N * 4)
         roof = {"bound": "hbm", "achieved": bytes_alg / (kern_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
         extra = {"packed_cols": int(info.n_units), "real_cols": real_cols, "tasks": int(info.n_tasks),
                  "split_windows": split_windows, "algorithmic_bytes": int(bytes_alg),
