@@ -170,6 +170,8 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
 # among kernels that are built and parity-tested) and the tile-width / tile-order sweeps, after the
 # paper's feature-by-feature study (Sections III-A..III-F, Table II) and its tile-width study (Section IV-C).
 ABLATION = [
+    ("no matrix cores: fp32 multiply-adds on the vector ALU (the generic kernel of the K-contiguous entry)",
+     {"ASP_BCSR_XT": "generic"}, {"workload_suffix": "_xt", "max_steps": 5}),
     ("MFMA, synchronous register-staged loads, one tile per workgroup, 128x256 tiles",
      {"ASP_BCSR_KERNEL": "regstage", "ASP_BCSR_BN": "256"}),
     ("+ direct-to-LDS ring, resident workgroups (2 per CU), static XCD-aware schedule, 128x256 tiles",
@@ -186,11 +188,14 @@ ABLATION = [
 def run_ablation(args):
     import subprocess
     rows = []
-    for label, env in ABLATION:
+    for entry in ABLATION:
+        label, env = entry[0], entry[1]
+        opt = entry[2] if len(entry) > 2 else {}
         e = dict(os.environ)
         e.update(env)
-        cmd = [sys.executable, os.path.abspath(__file__), "--workload", args.workload, "--also", "", "--no-cpu-baseline",
-               "--steps", str(args.steps), "--warmup", str(args.warmup)]
+        steps = min(args.steps, opt.get("max_steps", args.steps))
+        cmd = [sys.executable, os.path.abspath(__file__), "--workload", args.workload + opt.get("workload_suffix", ""),
+               "--also", "", "--no-cpu-baseline", "--steps", str(steps), "--warmup", str(min(args.warmup, steps))]
         out = subprocess.run(cmd, env=e, capture_output=True, text=True, timeout=600)
         if out.returncode != 0:
             rows.append({"variant": label, "switches": env, "error": out.stderr[-300:]})

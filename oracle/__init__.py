@@ -60,6 +60,8 @@ def _load():
     L.oracle_padded_width.restype = i64
     L.oracle_choose_bn.argtypes = [i64, vp, ctypes.c_int]
     L.oracle_choose_bn.restype = i64
+    L.oracle_choose_bn_weighted.argtypes = [i64, vp, vp, ctypes.c_int]
+    L.oracle_choose_bn_weighted.restype = i64
     _lib = L
     return L
 
@@ -150,3 +152,11 @@ def padded_width(N, BN) -> int:
 def choose_bn(N, candidates) -> int:
     c = np.ascontiguousarray(candidates, dtype=np.int64)
     return int(_load().oracle_choose_bn(N, _p(c), len(c)))
+
+
+def choose_bn_weighted(N, candidates, cost) -> int:
+    """Tile width with the least padded_width x cost per column (Section IV-C); ties: the larger."""
+    c = np.ascontiguousarray(candidates, dtype=np.int64)
+    w = np.ascontiguousarray(cost, dtype=np.int64)
+    assert len(c) == len(w)
+    return int(_load().oracle_choose_bn_weighted(N, _p(c), _p(w), len(c)))

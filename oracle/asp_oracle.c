@@ -297,3 +297,21 @@ int64_t oracle_choose_bn(int64_t N, const int64_t *candidates, int n_candidates)
     }
     return best;
 }
+
+/*
+ * Tile width by cost (Section IV-C: a wider tile does more work per loaded A tile, a tile that does not divide N
+ * computes on padding): the candidate with the smallest  padded_width(N, BN) x cost_per_column(BN); ties: the
+ * larger.  With equal costs this is oracle_choose_bn.
+ */
+int64_t oracle_choose_bn_weighted(int64_t N, const int64_t *candidates, const int64_t *cost, int n_candidates)
+{
+    int64_t best = -1, best_cost = -1;
+    for (int c = 0; c < n_candidates; ++c) {
+        int64_t total = oracle_padded_width(N, candidates[c]) * cost[c];
+        if (best < 0 || total < best_cost || (total == best_cost && candidates[c] > best)) {
+            best_cost = total;
+            best = candidates[c];
+        }
+    }
+    return best;
+}

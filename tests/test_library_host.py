@@ -199,15 +199,18 @@ def test_wcsr_converter_irregular_workloads():
             asp.asp_destroy(h)
 
 
+COST = [118, 89, 71, 64]   # the library's published cost per column of 64 / 128 / 256 / 512-wide tiles, in 1/64
+
+
 def test_plan_follows_tile_width_rule():
     a = synth.block_sparse_bernoulli(256, 256, 128, 128, 0.5, 1)
     h = asp.asp_create_from_csr("bcsr", "bf16", 128, 128, a.m, a.k, a.row_ptr, a.col_idx, a.values, flags=HOST)
     try:
-        for N in (64, 128, 192, 256, 320, 1024, 16384, 100, 72, 1):
+        for N in (64, 128, 192, 256, 320, 1024, 1104, 16384, 16448, 100, 72, 8, 1):
             p = asp.asp_plan_spmm(h, N)
             if N % 8 == 0:
                 assert p.vectorized == 1
-                assert p.bn == oracle.choose_bn(N, [64, 128, 256])
+                assert p.bn == oracle.choose_bn_weighted(N, [64, 128, 256], COST[:3])
             else:
                 assert p.vectorized == 0 and p.bn == 64
             assert p.n_tiles == -(-N // p.bn) and p.padded_n == oracle.padded_width(N, p.bn)
@@ -218,9 +221,9 @@ def test_plan_follows_tile_width_rule():
     a = synth.block_sparse_bernoulli(2048, 256, 128, 128, 0.0, 2)
     h = asp.asp_create_from_csr("bcsr", "bf16", 128, 128, a.m, a.k, a.row_ptr, a.col_idx, a.values, flags=HOST)
     try:
-        for N, cands in ((16384, [64, 128, 256, 512]), (8192, [64, 128, 256, 512]), (4096, [64, 128, 256]), (8192 + 64, [64, 128, 256, 512])):
+        for N, cands in ((16384, [64, 128, 256, 512]), (8192, [64, 128, 256, 512]), (4096, [64, 128, 256]), (8192 + 64, [64, 128, 256, 512]), (16448, [64, 128, 256, 512]), (1104, [64, 128, 256])):
             p = asp.asp_plan_spmm(h, N)
-            assert p.bn == oracle.choose_bn(N, cands), (N, p.bn)
+            assert p.bn == oracle.choose_bn_weighted(N, cands, COST[:len(cands)]), (N, p.bn)
     finally:
         asp.asp_destroy(h)
 

@@ -53,6 +53,16 @@ def test_golden_tile_width(golden_dir):
     assert oracle.choose_bn(1024, [352, 496]) == 352       # none divides: least padding
     assert oracle.choose_bn(192, [64, 128, 256]) == 64     # largest divisor, not largest width
     assert oracle.choose_bn(16384, [64, 128, 256]) == 256
+    # weighted form: equal costs give the plain rule; hand-computed cases with costs 118 / 89 / 71 / 64 per column
+    for N in (1, 8, 64, 100, 192, 200, 320, 1000, 1024, 1488, 16384, 16448):
+        assert oracle.choose_bn_weighted(N, [64, 128, 256], [1, 1, 1]) == oracle.choose_bn(N, [64, 128, 256])
+    cand, cost = [64, 128, 256, 512], [118, 89, 71, 64]
+    assert oracle.choose_bn_weighted(192, cand, cost) == 256     # 192*118 = 22656 > 256*89 = 22784 > 256*71 = 18176 < 512*64
+    assert oracle.choose_bn_weighted(64, cand, cost) == 64       # 64*118 = 7552 < 128*89
+    assert oracle.choose_bn_weighted(16448, cand, cost) == 512   # 16896*64 = 1081344 < 16640*71 < 16512*89 < 16448*118
+    assert oracle.choose_bn_weighted(320, cand, cost) == 512     # 512*64 = 32768 < 384*89 = 34176 < 512*71 < 320*118
+    assert oracle.choose_bn_weighted(1024, cand, cost) == 512
+    assert oracle.choose_bn_weighted(1100, cand, cost) == 256    # 1280*71 = 90880 < 1536*64 = 98304
 
 
 # ------------------------------------------------------------------ BCSR
