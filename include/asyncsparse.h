@@ -202,6 +202,22 @@ asp_status_t asp_mtx_get(const asp_mtx_t *mx, int64_t *m, int64_t *k, int64_t *n
                          const int32_t **col_idx, const float **values);
 asp_status_t asp_mtx_free(asp_mtx_t *mx);
 
+/*
+ * Measurement support: enqueue a kernel that does nothing but matrix-core instructions of the given dtype
+ * (v_mfma_f32_32x32x16_bf16 or v_mfma_f32_32x32x2_f32, register operands, two waves per SIMD on every compute
+ * unit) for `iters` rounds of 8 per wave, and report in *flop (HOST) how many floating-point operations that is.
+ * Timed by the caller around the launch, it gives the matrix-core rate this machine sustains, beside the published
+ * peak.  out_device: DEVICE, at least 4 bytes, never written in practice.  Asynchronous, allocates nothing.
+ */
+asp_status_t asp_probe_mfma(int32_t dtype, int64_t iters, void *out_device, void *stream, double *flop);
+
+/*
+ * Measurement support: enqueue a kernel that only reads `bytes` (rounded down to 16) of DEVICE memory at
+ * src_device (16-byte aligned) with 16-byte loads -- the read-only stream that a gather-bound kernel is compared
+ * with.  out_device: DEVICE, at least 4 bytes.  Asynchronous, allocates nothing.
+ */
+asp_status_t asp_probe_read(const void *src_device, int64_t bytes, void *out_device, void *stream);
+
 /* host only */
 const char *asp_status_string(asp_status_t s);
 const char *asp_last_error(void);

@@ -207,6 +207,19 @@ asp_status_t asp_spmm_xt(const asp_handle_t *h, const void *X, void *Y, int64_t 
     return bcsr_spmm_xt_launch(h, X, Y, N, (hipStream_t)stream);
 }
 
+asp_status_t asp_probe_mfma(int32_t dtype, int64_t iters, void *out_device, void *stream, double *flop) {
+    if (!out_device || !flop) return fail(ASP_ERR_INVALID_ARG, "null out_device or flop");
+    if (dtype != ASP_DT_BF16 && dtype != ASP_DT_F32) return fail(ASP_ERR_INVALID_ARG, "unknown dtype");
+    if (iters < 1 || iters > (1 << 24)) return fail(ASP_ERR_INVALID_ARG, "iters out of range");
+    return probe_mfma_launch(dtype, iters, out_device, (hipStream_t)stream, flop);
+}
+
+asp_status_t asp_probe_read(const void *src_device, int64_t bytes, void *out_device, void *stream) {
+    if (!src_device || !out_device) return fail(ASP_ERR_INVALID_ARG, "null src_device or out_device");
+    if (bytes < 16 || ((uintptr_t)src_device & 15)) return fail(ASP_ERR_INVALID_ARG, "need at least 16 bytes, 16-byte aligned");
+    return probe_read_launch(src_device, bytes, out_device, (hipStream_t)stream);
+}
+
 asp_status_t asp_get_info(const asp_handle_t *h, asp_info_t *info) {
     if (!h || !info) return fail(ASP_ERR_INVALID_ARG, "null handle or info");
     info->m = h->m;
