@@ -659,3 +659,22 @@ def test_measurement_probes_run_and_count_their_work():
     L = asp.lib()
     assert L.asp_probe_read(x.data_ptr() + 4, 64, out.data_ptr(), None) == asp.ASP_ERR_INVALID_ARG
     assert L.asp_probe_mfma(7, 10, out.data_ptr(), None, None) == asp.ASP_ERR_INVALID_ARG
+
+
+# ------------------------------------------------------------------ the widened rows at the full benchmark shapes
+@pytest.mark.parametrize("name", ["bcsr_gate_proj_f32", "bcsr_gate_proj_b64", "bcsr_down_proj_b32"])
+def test_bcsr_other_precision_and_block_sizes_full_size_sampled_columns(name):
+    a, fmt, br, bc, N, dt, seedB = synth.workload(name)
+    B = synth.dense_normal(a.k, N, dt, seedB)
+    C = gpu_spmm(a, fmt, br, bc, B)
+    check_against_oracle(a, B, C, _sample_columns(N, 256, np.random.default_rng(4)))
+
+
+def test_bcsr_xt_config2_full_size_sampled_tokens():
+    # the K-contiguous entry at the benchmark shape: every output feature of 128 sampled tokens (first and last tile,
+    # two interior slices) -- a token's outputs depend on that token's row of X only
+    a, fmt, br, bc, N, dt, seedB = synth.workload("bcsr_gate_proj")
+    X = synth.dense_normal(N, a.k, dt, seedB)
+    Y = gpu_spmm_xt(a, br, X)
+    tok = _sample_columns(N, 512, np.random.default_rng(5))
+    check_against_oracle(a, np.ascontiguousarray(X[tok].T), np.ascontiguousarray(Y[tok].T))
