@@ -678,3 +678,25 @@ def test_bcsr_xt_config2_full_size_sampled_tokens():
     Y = gpu_spmm_xt(a, br, X)
     tok = _sample_columns(N, 512, np.random.default_rng(5))
     check_against_oracle(a, np.ascontiguousarray(X[tok].T), np.ascontiguousarray(Y[tok].T))
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_random_configurations_parity(seed):
+    # seeded draw over format, precision, sizes, density, block / window size, task size, alignment and scratch
+    rng = np.random.default_rng(7000 + seed)
+    fmt = str(rng.choice(["bcsr", "wcsr"]))
+    dt = str(rng.choice(["bf16", "f32"]))
+    m, k = int(rng.integers(1, 700)), int(rng.integers(1, 700))
+    N = int(rng.choice([1, 3, 8, 17, 32, 64, 72, 100, 128, 136, 200, 256, 264, 384, 520]))
+    dens = float(rng.choice([0.0, 0.002, 0.01, 0.05, 0.2, 0.6]))
+    if fmt == "bcsr":
+        br = bc = int(rng.choice([32, 64, 128]))
+        tc = 0
+    else:
+        br, bc, tc = int(rng.choice([16, 32, 64])), 8, int(rng.choice([0, 8, 16, 40, 512]))
+    mis = bool(rng.random() < 0.15)
+    reserve = bool(rng.random() < 0.7) or dt == "bf16"
+    a = synth.random_csr(m, k, dens, seed=8000 + seed, dtype=dt, empty_row_frac=float(rng.choice([0, 0.3])), dist="normal")
+    B = synth.dense_normal(k, N, dt, seed=9000 + seed)
+    C = gpu_spmm(a, fmt, br, bc, B, task_cols=tc, misalign=mis, reserve=reserve)
+    check_against_oracle(a, B, C)
