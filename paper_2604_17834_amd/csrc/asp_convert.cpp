@@ -164,6 +164,10 @@ void bcsr_build_schedule(HostBcsr &b) {
         lists[best].push_back(sorted[r]);
         load[best] += len(sorted[r]) + 1;
     }
+    // Lists with one entry more go first, so that the entries of the last, incomplete round are those of lists
+    // 0, 1, ... and "entry j belongs to list j % LISTS" holds for every j.
+    std::stable_sort(lists.begin(), lists.end(),
+                     [](const std::vector<int32_t> &x, const std::vector<int32_t> &y) { return x.size() > y.size(); });
     // Inside a list the order is free (the sum stays).  Entries go by the block column of their first block:
     // the block-rows of one round then start in the same few block columns, their first slabs of B are requested
     // by several workgroups of the XCD at about the same time and cross the memory side of L2 once
