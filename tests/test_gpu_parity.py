@@ -700,3 +700,21 @@ def test_random_configurations_parity(seed):
     B = synth.dense_normal(k, N, dt, seed=9000 + seed)
     C = gpu_spmm(a, fmt, br, bc, B, task_cols=tc, misalign=mis, reserve=reserve)
     check_against_oracle(a, B, C)
+
+
+def test_create_reserve_destroy_returns_device_memory():
+    a = synth.zipf_graph(20000, 20000, 12 * 20000, seed=90, cap=3000, dtype="bf16")
+    b = synth.block_sparse_bernoulli(1024, 1024, 64, 64, 0.7, seed=91)
+    free0 = None
+    for it in range(21):
+        if it == 1:   # the first round also pays the runtime's one-time allocations
+            torch.cuda.synchronize()
+            free0 = torch.cuda.mem_get_info()[0]
+        h = asp.asp_create_from_csr("wcsr", "bf16", 16, 8, a.m, a.k, a.row_ptr, a.col_idx, a.values, task_cols=64)
+        asp.asp_reserve(h, 64)
+        asp.asp_reserve(h, 256)     # grows: the smaller buffer is freed
+        asp.asp_destroy(h)
+        h = asp.asp_create_from_csr("bcsr", "bf16", 64, 64, b.m, b.k, b.row_ptr, b.col_idx, b.values)
+        asp.asp_destroy(h)
+    torch.cuda.synchronize()
+    assert abs(torch.cuda.mem_get_info()[0] - free0) < (8 << 20)
