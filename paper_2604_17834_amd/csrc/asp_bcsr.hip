@@ -33,6 +33,8 @@ typedef __attribute__((ext_vector_type(4))) short short4v;
 typedef __attribute__((ext_vector_type(8))) short short8v;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;  // staging registers: a plain vector type, so that
+                                                                 // arrays of it are split into registers
 
 template <int BR, int BC, int BN, int WM, int WN, bool VEC>
 struct BcsrCfg {
@@ -60,12 +62,12 @@ struct BcsrCfg {
     static_assert(BC % KS == 0, "block width must be a multiple of the stage depth");
 };
 
-__device__ __forceinline__ uint4 load_b_chunk_scalar(const uint16_t *__restrict__ B, int64_t row_off, int col, int N) {
+__device__ __forceinline__ u32x4 load_b_chunk_scalar(const uint16_t *__restrict__ B, int64_t row_off, int col, int N) {
     // slow path: N or the base pointers do not allow 16-byte accesses
     uint16_t e[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) e[i] = (col + i < N) ? B[row_off + col + i] : (uint16_t)0;
-    uint4 v;
+    u32x4 v;
     v.x = e[0] | ((uint32_t)e[1] << 16);
     v.y = e[2] | ((uint32_t)e[3] << 16);
     v.z = e[4] | ((uint32_t)e[5] << 16);
@@ -106,11 +108,11 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void bcsr_spmm_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    uint4 ra[Cfg::A_LD], rb[Cfg::B_LD];
+    u32x4 ra[Cfg::A_LD], rb[Cfg::B_LD];
 
     auto load_stage = [&](int t) {
         const int p = blk0 + t / Cfg::SPB, s = t % Cfg::SPB;
-        const uint4 *asrc = (const uint4 *)(a_packed + (int64_t)p * (BR * BC) + (int64_t)s * (BR * KS));
+        const u32x4 *asrc = (const u32x4 *)(a_packed + (int64_t)p * (BR * BC) + (int64_t)s * (BR * KS));
 #pragma unroll
         for (int i = 0; i < Cfg::A_LD; ++i) {
             int c = i * NT + tid;
@@ -123,10 +125,10 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void bcsr_spmm_kernel(
             if (Cfg::B_CHUNKS % NT == 0 || c < Cfg::B_CHUNKS) {
                 int r = c / Cfg::B_CPR, cc = c % Cfg::B_CPR;
                 int krow = krow0 + r, col = n0 + cc * 8;
-                uint4 v = make_uint4(0, 0, 0, 0);
+                u32x4 v = {0u, 0u, 0u, 0u};
                 if (krow < K && col < N) {  // rows past K belong to the zero padding of the last block column
                     if (VEC)
-                        v = *(const uint4 *)(B + (int64_t)krow * N + col);
+                        v = *(const u32x4 *)(B + (int64_t)krow * N + col);
                     else
                         v = load_b_chunk_scalar(B, (int64_t)krow * N, col, N);
                 }
@@ -139,14 +141,14 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void bcsr_spmm_kernel(
 #pragma unroll
         for (int i = 0; i < Cfg::A_LD; ++i) {
             int c = i * NT + tid;
-            if (Cfg::A_CHUNKS % NT == 0 || c < Cfg::A_CHUNKS) *(uint4 *)(sa + c * 16) = ra[i];
+            if (Cfg::A_CHUNKS % NT == 0 || c < Cfg::A_CHUNKS) *(u32x4 *)(sa + c * 16) = ra[i];
         }
 #pragma unroll
         for (int i = 0; i < Cfg::B_LD; ++i) {
             int c = i * NT + tid;
             if (Cfg::B_CHUNKS % NT == 0 || c < Cfg::B_CHUNKS) {
                 int r = c / Cfg::B_CPR, cc = c % Cfg::B_CPR;
-                *(uint4 *)(sb + r * Cfg::PB + cc * 16) = rb[i];
+                *(u32x4 *)(sb + r * Cfg::PB + cc * 16) = rb[i];
             }
         }
     };

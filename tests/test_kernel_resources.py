@@ -15,6 +15,7 @@ HIPCC = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
 
 HOT = {
     "asp_bcsr_wide.hip": ["bcsr_spmm_wide_kernel"],
+    "asp_bcsr.hip": ["bcsr_spmm_kernel"],
     "asp_bcsr_dma.hip": ["bcsr_spmm_dma_kernel"],
     "asp_bcsr_f32.hip": ["bcsr_f32_spmm_kernel"],
     "asp_wcsr.hip": ["wcsr16_spmm_kernel", "wcsr32_spmm_kernel"],
