@@ -173,7 +173,9 @@ asp_status_t asp_destroy(asp_handle_t *h);
  * Reverse Cuthill-McKee ordering of a square m x m matrix given as CSR structure (HOST arrays, valid sorted
  * CSR as for asp_create_from_csr).  The structure is taken as that of A + A^T.  perm (HOST, m entries,
  * written) receives perm[new] = old.  Every connected component is numbered breadth-first from its node of
- * least degree, neighbours in order of degree (ties: lower index), and the numbering is reversed.
+ * least degree, neighbours in order of degree (ties: lower index), and the numbering is reversed.  A node's
+ * degree is its number of neighbours in A + A^T, a stored diagonal entry counting twice (the convention of the
+ * scipy routine the paper uses).
  */
 asp_status_t asp_rcm(int64_t m, const int32_t *row_ptr, const int32_t *col_idx, int32_t *perm);
 
