@@ -50,6 +50,11 @@ typedef enum { ASP_DT_BF16 = 0, ASP_DT_F32 = 1 } asp_dtype_t;
  * without a GPU.  The handle can be inspected (info/export/plan) but asp_spmm refuses it. */
 #define ASP_FLAG_HOST_CONVERT_ONLY 1u
 
+/* Largest dense width N (columns of B and C; tokens of asp_spmm_xt) that any call accepts: 65535 column tiles
+ * of 64.  Beyond it calls return ASP_ERR_UNSUPPORTED (asp_reserve, asp_plan_spmm: ASP_ERR_INVALID_ARG).
+ * M x N (and K x N for asp_spmm_xt) must also stay below 2^40 elements. */
+#define ASP_MAX_N (65535ll * 64)
+
 typedef struct {
     int32_t format;    /* asp_format_t */
     int32_t dtype;     /* asp_dtype_t; both dtypes are built for both formats */
@@ -115,7 +120,7 @@ asp_status_t asp_create_from_csr(const asp_config_t *cfg, int64_t m, int64_t k, 
  * C = A x B (Section II-C; kernels: Sections III-A..III-C re-designed for gfx950).
  * B: DEVICE, k x N row-major, leading dimension N.  C: DEVICE, m x N row-major, leading dimension N,
  * fully overwritten (rows of A without entries become zeros); C must not alias B.
- * N >= 1.  stream: hipStream_t (NULL = default).  Asynchronous: only enqueues kernels, never
+ * 1 <= N <= ASP_MAX_N.  stream: hipStream_t (NULL = default).  Asynchronous: only enqueues kernels, never
  * synchronises, never allocates.  bf16: fp32 accumulation, round-to-nearest-even to bf16 on store.
  * f32: fp32 products and sums on the matrix cores (no reduced-precision operand formats).
  * WCSR windows that are split into several tasks: with scratch memory (asp_reserve) the tasks' fp32 partial
@@ -143,7 +148,7 @@ asp_status_t asp_reserve(asp_handle_t *h, int64_t N);
  * the layout of the paper's LLM case study (Section IV-D: C = W X^T, activations stored tokens x hidden),
  * so that projections can be chained without transposes.
  * X: DEVICE, N x k row-major (leading dimension k).  Y: DEVICE, N x m row-major (leading dimension m), fully
- * overwritten; Y must not alias X.  N >= 1.  BCSR handles (bf16) only; others return ASP_ERR_UNSUPPORTED.
+ * overwritten; Y must not alias X.  1 <= N <= ASP_MAX_N.  BCSR handles (bf16) only; others return ASP_ERR_UNSUPPORTED.
  * Asynchronous, never synchronises, never allocates.  fp32 accumulation, round-to-nearest-even to bf16;
  * bitwise reproducible.  128x128 blocks with k % 8 == 0, m % 8 == 0, 16-byte aligned X and Y and at least
  * one 128 x 512 tile per compute unit run on the matrix cores; everything else takes a slow generic kernel.

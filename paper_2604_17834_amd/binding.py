@@ -21,6 +21,7 @@ ASP_FMT_BCSR, ASP_FMT_WCSR = 0, 1
 ASP_DT_BF16, ASP_DT_F32 = 0, 1
 ASP_ARR_ROW_PTR, ASP_ARR_COL_IDX, ASP_ARR_VALUES, ASP_ARR_TASKS = 0, 1, 2, 3
 ASP_FLAG_HOST_CONVERT_ONLY = 1
+ASP_MAX_N = 65535 * 64   # largest dense width any call accepts
 
 _FMT = {"bcsr": ASP_FMT_BCSR, "wcsr": ASP_FMT_WCSR}
 _DT = {"bf16": ASP_DT_BF16, "f32": ASP_DT_F32}

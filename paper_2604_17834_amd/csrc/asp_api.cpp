@@ -78,7 +78,10 @@ static asp_status_t create_impl(const asp_config_t *cfg, int64_t m, int64_t k, i
 
     // WCSR
     h->task_cols = cfg->task_cols > 0 ? cfg->task_cols : 512;
-    csr_to_wcsr(m, k, row_ptr, col_idx, values, es, cfg->b_row, cfg->b_col, h->hw);
+    if (!csr_to_wcsr(m, k, row_ptr, col_idx, values, es, cfg->b_row, cfg->b_col, h->hw)) {
+        set_error("the packed columns of all windows, padded to multiples of b_col, exceed 2^31 - 1");
+        return ASP_ERR_UNSUPPORTED;
+    }
     h->n_units = (int64_t)h->hw.window_col_idx.size();
     wcsr_zero_windows(h->hw.window_row_ptr, h->task_cols, h->hw.zero_windows);
     h->n_zero_windows = (int64_t)h->hw.zero_windows.size();
@@ -170,14 +173,14 @@ asp_status_t asp_spmm(const asp_handle_t *h, const void *B, void *C, int64_t N, 
     if (!h || !B || !C) return fail(ASP_ERR_INVALID_ARG, "null handle, B or C");
     if (N < 1) return fail(ASP_ERR_INVALID_ARG, "N must be >= 1");
     if (h->device < 0) return fail(ASP_ERR_UNSUPPORTED, "handle was converted on the host only; it has no device arrays");
-    if (N >= (1ll << 31) || h->m * N >= (1ll << 40)) return fail(ASP_ERR_UNSUPPORTED, "N too large");
+    if (N > ASP_MAX_N || h->m * N >= (1ll << 40)) return fail(ASP_ERR_UNSUPPORTED, "N too large (ASP_MAX_N, and M x N below 2^40)");
     if (h->format == ASP_FMT_BCSR) return bcsr_spmm_launch(h, B, C, N, (hipStream_t)stream);
     return wcsr_spmm_launch(h, B, C, N, (hipStream_t)stream);
 }
 
 asp_status_t asp_reserve(asp_handle_t *h, int64_t N) {
     if (!h) return fail(ASP_ERR_INVALID_ARG, "null handle");
-    if (N < 1 || N >= (1ll << 31)) return fail(ASP_ERR_INVALID_ARG, "N out of range");
+    if (N < 1 || N > ASP_MAX_N) return fail(ASP_ERR_INVALID_ARG, "N out of range (1 .. ASP_MAX_N)");
     if (h->device < 0) return fail(ASP_ERR_UNSUPPORTED, "handle was converted on the host only; it has no device arrays");
     if (h->format != ASP_FMT_WCSR || h->n_split_tasks == 0) return ASP_OK;  // uses none
     const int64_t need = wcsr_scratch_floats(h, N);
@@ -203,7 +206,8 @@ asp_status_t asp_spmm_xt(const asp_handle_t *h, const void *X, void *Y, int64_t 
     if (h->device < 0) return fail(ASP_ERR_UNSUPPORTED, "handle was converted on the host only; it has no device arrays");
     if (h->format != ASP_FMT_BCSR || h->dtype != ASP_DT_BF16)
         return fail(ASP_ERR_UNSUPPORTED, "the K-contiguous entry is built for bf16 BCSR handles only");
-    if (N >= (1ll << 31) || h->m * N >= (1ll << 40) || h->k * N >= (1ll << 40)) return fail(ASP_ERR_UNSUPPORTED, "N too large");
+    if (N > ASP_MAX_N || h->m * N >= (1ll << 40) || h->k * N >= (1ll << 40))
+        return fail(ASP_ERR_UNSUPPORTED, "N too large (ASP_MAX_N, and M x N, K x N below 2^40)");
     return bcsr_spmm_xt_launch(h, X, Y, N, (hipStream_t)stream);
 }
 
@@ -242,7 +246,7 @@ asp_status_t asp_get_info(const asp_handle_t *h, asp_info_t *info) {
 
 asp_status_t asp_plan_spmm(const asp_handle_t *h, int64_t N, asp_plan_t *plan) {
     if (!h || !plan) return fail(ASP_ERR_INVALID_ARG, "null handle or plan");
-    if (N < 1 || N >= (1ll << 31)) return fail(ASP_ERR_INVALID_ARG, "N out of range");
+    if (N < 1 || N > ASP_MAX_N) return fail(ASP_ERR_INVALID_ARG, "N out of range (1 .. ASP_MAX_N)");
     if (h->format == ASP_FMT_BCSR) {
         BcsrPlan p = bcsr_plan(h, N, true);
         plan->bn = p.bn;

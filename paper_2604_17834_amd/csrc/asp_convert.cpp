@@ -5,6 +5,7 @@
 // windows do not serialise the conversion.
 #include <algorithm>
 #include <atomic>
+#include <cstdint>
 #include <cstdlib>
 #include <cstring>
 #include <thread>
@@ -250,60 +251,81 @@ void bcsr_pack_fragments_f32(const HostBcsr &in, int32_t b_row, int32_t b_col, s
 // ------------------------------------------------------------------------------------------ WCSR
 namespace {
 
-// Merge the (sorted) rows of one window.  emit(t, col) is called once per distinct column in ascending
-// order with its rank t; hit(t, row_in_window, p) once per CSR entry p that sits in that column.
-template <class Emit, class Hit>
-int64_t merge_window(const int32_t *row_ptr, const int32_t *col_idx, int64_t r0, int64_t r1, int32_t k,
-                     Emit emit, Hit hit) {
-    int64_t head[64], end[64];
-    const int nr = (int)(r1 - r0);
-    for (int r = 0; r < nr; ++r) {
-        head[r] = row_ptr[r0 + r];
-        end[r] = row_ptr[r0 + r + 1];
+// Columns of one window, ascending with duplicates between rows removed: sort the window's CSR entries (they
+// are one contiguous range of col_idx) by column.  A k-way merge of the sorted rows costs rows x distinct
+// columns and was 30x slower for 64-row windows with ~1000 columns.
+// key = column << 32 | entry index inside the window (the window's entries are fewer than 2^31).
+struct WindowSorter {
+    std::vector<uint64_t> key;
+    std::vector<uint8_t> row_of;  // row inside the window of each entry
+
+    // distinct columns only
+    int64_t count(const int32_t *row_ptr, const int32_t *col_idx, int64_t r0, int64_t r1) {
+        const int64_t p0 = row_ptr[r0], n = row_ptr[r1] - p0;
+        if (r1 - r0 == 1) return n;  // a row's columns are distinct already
+        key.resize((size_t)n);
+        for (int64_t e = 0; e < n; ++e) key[e] = (uint32_t)col_idx[p0 + e];
+        std::sort(key.begin(), key.end());
+        return (int64_t)(std::unique(key.begin(), key.end()) - key.begin());
     }
-    int64_t t = 0;
-    for (;;) {
-        int32_t cmin = k;  // larger than any valid column
-        for (int r = 0; r < nr; ++r)
-            if (head[r] < end[r] && col_idx[head[r]] < cmin) cmin = col_idx[head[r]];
-        if (cmin == k) break;
-        emit(t, cmin);
-        for (int r = 0; r < nr; ++r)
-            if (head[r] < end[r] && col_idx[head[r]] == cmin) {
-                hit(t, r, head[r]);
-                ++head[r];
+
+    // emit(t, col) once per distinct column in ascending order with its rank t; hit(t, row_in_window, p) once
+    // per CSR entry p that sits in that column
+    template <class Emit, class Hit>
+    void place(const int32_t *row_ptr, const int32_t *col_idx, int64_t r0, int64_t r1, Emit emit, Hit hit) {
+        const int64_t p0 = row_ptr[r0], n = row_ptr[r1] - p0;
+        key.resize((size_t)n);
+        row_of.resize((size_t)n);
+        for (int64_t r = r0; r < r1; ++r)
+            for (int64_t p = row_ptr[r]; p < row_ptr[r + 1]; ++p) {
+                key[p - p0] = ((uint64_t)(uint32_t)col_idx[p] << 32) | (uint64_t)(p - p0);
+                row_of[p - p0] = (uint8_t)(r - r0);
             }
-        ++t;
+        std::sort(key.begin(), key.end());
+        int64_t t = -1;
+        int32_t prev = -1;
+        for (int64_t i = 0; i < n; ++i) {
+            const int32_t col = (int32_t)(key[i] >> 32);
+            const int64_t e = (int64_t)(key[i] & 0xFFFFFFFFu);
+            if (col != prev) {
+                emit(++t, col);
+                prev = col;
+            }
+            hit(t, (int)row_of[e], p0 + e);
+        }
     }
-    return t;
-}
+};
 
 }  // namespace
 
-void csr_to_wcsr(int64_t m, int64_t k, const int32_t *row_ptr, const int32_t *col_idx, const void *values,
+bool csr_to_wcsr(int64_t m, int64_t k, const int32_t *row_ptr, const int32_t *col_idx, const void *values,
                  size_t esize, int32_t b_row, int32_t b_col, HostWcsr &out) {
+    (void)k;
     const int64_t nw = ceil_div(m, b_row);
     out.window_row_ptr.assign(nw + 1, 0);
     parallel_chunks(nw, 64, [&](unsigned, int64_t b, int64_t e) {
+        WindowSorter ws;
         for (int64_t w = b; w < e; ++w) {
             int64_t r0 = w * b_row, r1 = std::min<int64_t>(m, r0 + b_row);
-            int64_t u = merge_window(row_ptr, col_idx, r0, r1, (int32_t)k, [](int64_t, int32_t) {},
-                                     [](int64_t, int, int64_t) {});
+            int64_t u = ws.count(row_ptr, col_idx, r0, r1);
             out.window_row_ptr[w + 1] = (int32_t)(ceil_div(u, b_col) * b_col);
         }
     });
+    int64_t total = 0;  // packed positions are 32-bit: padding can push them past what the entries needed
+    for (int64_t w = 0; w < nw; ++w) total += out.window_row_ptr[w + 1];
+    if (total > INT32_MAX) return false;
     for (int64_t w = 0; w < nw; ++w) out.window_row_ptr[w + 1] += out.window_row_ptr[w];
     const int64_t padded = out.window_row_ptr[nw];
     out.window_col_idx.assign(padded, -1);
-    out.values.assign((size_t)padded * b_row * esize, 0);
+    out.values.reset((size_t)padded * b_row * esize);
     const int64_t tile = (int64_t)b_row * b_col;
     parallel_chunks(nw, 64, [&](unsigned, int64_t b, int64_t e) {
+        WindowSorter ws;
         for (int64_t w = b; w < e; ++w) {
             int64_t r0 = w * b_row, r1 = std::min<int64_t>(m, r0 + b_row);
             const int64_t p0 = out.window_row_ptr[w];
-            merge_window(
-                row_ptr, col_idx, r0, r1, (int32_t)k,
-                [&](int64_t t, int32_t col) { out.window_col_idx[p0 + t] = col; },
+            ws.place(
+                row_ptr, col_idx, r0, r1, [&](int64_t t, int32_t col) { out.window_col_idx[p0 + t] = col; },
                 [&](int64_t t, int r, int64_t p) {
                     int64_t pc = p0 + t;
                     size_t dst = (size_t)((pc / b_col) * tile + (int64_t)r * b_col + pc % b_col) * esize;
@@ -311,6 +333,7 @@ void csr_to_wcsr(int64_t m, int64_t k, const int32_t *row_ptr, const int32_t *co
                 });
         }
     });
+    return true;
 }
 
 void wcsr_tasks_host(const std::vector<int32_t> &wrp, int32_t task_cols, std::vector<int32_t> &tasks) {

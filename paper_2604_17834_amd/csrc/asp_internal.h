@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <cstdlib>
+#include <new>
 #include <string>
 #include <vector>
 
@@ -27,6 +29,40 @@ inline size_t dtype_size(int32_t dt) { return dt == ASP_DT_BF16 ? 2 : 4; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // ---- host-side converted forms -------------------------------------------------------------
+// Zero-filled byte buffer taken from calloc: for gigabytes the pages arrive zeroed from the system and are first
+// touched by the converter's worker threads, where a std::vector would fill them on one thread first.
+class ZeroedBytes {
+public:
+    ZeroedBytes() = default;
+    ZeroedBytes(const ZeroedBytes &) = delete;
+    ZeroedBytes &operator=(const ZeroedBytes &) = delete;
+    ZeroedBytes(ZeroedBytes &&o) noexcept : p_(o.p_), n_(o.n_) { o.p_ = nullptr, o.n_ = 0; }
+    ZeroedBytes &operator=(ZeroedBytes &&o) noexcept {
+        if (this != &o) {
+            std::free(p_);
+            p_ = o.p_, n_ = o.n_;
+            o.p_ = nullptr, o.n_ = 0;
+        }
+        return *this;
+    }
+    ~ZeroedBytes() { std::free(p_); }
+    void reset(size_t bytes) {
+        std::free(p_);
+        p_ = nullptr, n_ = 0;
+        if (bytes == 0) return;
+        p_ = (uint8_t *)std::calloc(bytes, 1);
+        if (!p_) throw std::bad_alloc();
+        n_ = bytes;
+    }
+    uint8_t *data() { return p_; }
+    const uint8_t *data() const { return p_; }
+    size_t size() const { return n_; }
+
+private:
+    uint8_t *p_ = nullptr;
+    size_t n_ = 0;
+};
+
 struct HostBcsr {
     std::vector<int32_t> block_row_ptr;  // [n_brows + 1]
     std::vector<int32_t> block_col_idx;  // [nnz_blocks]
@@ -42,7 +78,7 @@ struct HostBcsr {
 struct HostWcsr {
     std::vector<int32_t> window_row_ptr;  // [n_windows + 1]
     std::vector<int32_t> window_col_idx;  // [padded_cols]
-    std::vector<uint8_t> values;          // [padded_cols / b_col][b_row][b_col], raw bytes
+    ZeroedBytes values;                   // [padded_cols / b_col][b_row][b_col], raw bytes
     std::vector<int32_t> tasks;           // [n_tasks][4]; filled on the host only in host-convert mode
     std::vector<int32_t> zero_windows;    // windows whose C rows must be cleared (empty or split)
     std::vector<int32_t> ws_slot;         // [n_windows] first scratch slot of a split window (one per task), -1 for the others
@@ -54,7 +90,7 @@ void csr_to_bcsr(int64_t m, int64_t k, const int32_t *row_ptr, const int32_t *co
 void bcsr_build_schedule(HostBcsr &b);
 void bcsr_pack_fragments_bf16(const HostBcsr &in, int32_t b_row, int32_t b_col, std::vector<uint8_t> &packed);
 void bcsr_pack_fragments_f32(const HostBcsr &in, int32_t b_row, int32_t b_col, std::vector<uint8_t> &packed);
-void csr_to_wcsr(int64_t m, int64_t k, const int32_t *row_ptr, const int32_t *col_idx, const void *values,
+bool csr_to_wcsr(int64_t m, int64_t k, const int32_t *row_ptr, const int32_t *col_idx, const void *values,
                  size_t esize, int32_t b_row, int32_t b_col, HostWcsr &out);
 void wcsr_tasks_host(const std::vector<int32_t> &window_row_ptr, int32_t task_cols, std::vector<int32_t> &tasks);
 void wcsr_zero_windows(const std::vector<int32_t> &window_row_ptr, int32_t task_cols,

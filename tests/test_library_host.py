@@ -228,6 +228,55 @@ def test_plan_follows_tile_width_rule():
         asp.asp_destroy(h)
 
 
+def test_dense_width_limit_is_the_headers_and_is_enforced():
+    hdr = open(os.path.join(os.path.dirname(__file__), "..", "include", "asyncsparse.h")).read()
+    mm = re.search(r"#define ASP_MAX_N \((\d+)ll \* (\d+)\)", hdr)
+    assert mm and int(mm.group(1)) * int(mm.group(2)) == asp.ASP_MAX_N
+    a = synth.block_sparse_bernoulli(256, 256, 64, 64, 0.5, 4)
+    h = asp.asp_create_from_csr("bcsr", "bf16", 64, 64, a.m, a.k, a.row_ptr, a.col_idx, a.values, flags=HOST)
+    try:
+        assert asp.asp_plan_spmm(h, asp.ASP_MAX_N).n_tiles >= 1
+        with pytest.raises(asp.AspError) as e:
+            asp.asp_plan_spmm(h, asp.ASP_MAX_N + 1)
+        assert e.value.status == asp.ASP_ERR_INVALID_ARG
+    finally:
+        asp.asp_destroy(h)
+
+
+def test_wcsr_conversion_does_not_depend_on_row_grouping():
+    # the window's columns come from sorting its entries: rows with shared, disjoint and interleaved columns,
+    # empty rows, a ragged last window, all window heights -- bit-exact against the oracle's converter
+    rng = np.random.default_rng(77)
+    m, k = 203, 5000
+    rows = []
+    for i in range(m):
+        kind = i % 5
+        if kind == 0:
+            c = np.array([], np.int64)
+        elif kind == 1:
+            c = np.arange(0, 4000, 7)                      # shared by every such row
+        elif kind == 2:
+            c = np.arange(i, k, 211)                       # disjoint between rows
+        elif kind == 3:
+            c = np.sort(rng.choice(k, 300, replace=False))
+        else:
+            c = np.array([k - 1 - (i % 3)])
+        rows.append(c)
+    row_ptr = np.zeros(m + 1, np.int32)
+    row_ptr[1:] = np.cumsum([len(c) for c in rows])
+    col_idx = np.concatenate(rows).astype(np.int32)
+    values = rng.uniform(-1, 1, len(col_idx)).astype(np.float32)
+    for b_row in (16, 32, 64):
+        wrp, wci, vals = oracle.to_wcsr(m, k, row_ptr, col_idx, values, "f32", b_row, 8)
+        h = asp.asp_create_from_csr("wcsr", "f32", b_row, 8, m, k, row_ptr, col_idx, values, flags=HOST)
+        try:
+            assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_ROW_PTR), wrp)
+            assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_COL_IDX), wci)
+            assert np.array_equal(asp.asp_export(h, asp.ASP_ARR_VALUES).view(np.uint32).ravel(), vals.view(np.uint32).ravel())
+        finally:
+            asp.asp_destroy(h)
+
+
 def test_spmm_entries_refuse_host_only_handles_and_null_pointers():
     a = synth.block_sparse_bernoulli(256, 256, 128, 128, 0.5, 3)
     h = asp.asp_create_from_csr("bcsr", "bf16", 128, 128, a.m, a.k, a.row_ptr, a.col_idx, a.values, flags=HOST)
