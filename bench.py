@@ -44,6 +44,18 @@ def _measured_traffic(workload):
     return None
 
 
+_DENSE_MEMO = {}
+
+
+def _dense_normal(synth, rows, cols, dt, seed):
+    """synth.dense_normal, keeping the last operand: the sweeps reuse one 1 GB operand for many matrices."""
+    key = (rows, cols, dt, seed)
+    if key not in _DENSE_MEMO:
+        _DENSE_MEMO.clear()
+        _DENSE_MEMO[key] = synth.dense_normal(rows, cols, dt, seed)
+    return _DENSE_MEMO[key]
+
+
 def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
     import numpy as np
 
@@ -60,7 +72,7 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
         rp, ci, va = asp.asp_permute_csr(a.m, a.k, a.row_ptr, a.col_idx, a.values, dt, perm, perm)
         a = synth.Csr(a.m, a.k, rp, ci, va, dt)
         t_reorder = time.time() - t1
-    B = synth.dense_normal(N, a.k, dt, seedB) if xt else synth.dense_normal(a.k, N, dt, seedB)
+    B = _dense_normal(synth, N, a.k, dt, seedB) if xt else _dense_normal(synth, a.k, N, dt, seedB)
     t_gen = time.time() - t0
     spmm = asp.asp_spmm_xt if xt else asp.asp_spmm
 
@@ -206,6 +218,26 @@ def run_ablation(args):
     print(json.dumps({"ablation": rows, "workload": args.workload, "steps": args.steps}))
 
 
+# Config 5 (8192 x 8192, geometric block-row lengths, N = 65536: every block size and sparsity) and config 4
+# (band + 64 long rows, 2e6 rows) at both dense widths: measured points that are not bench lines.
+SWEEP = ["bcsr_sweep_b%d_s%d" % (b, p) for b in (128, 64, 32) for p in (50, 75, 90, 95, 99)] + \
+        ["wcsr_band_dense_rows", "wcsr_band_dense_rows_n256", "wcsr_band_dense_rows_bf16", "wcsr_band_dense_rows_n256_bf16"]
+
+
+def run_sweep(args, torch, asp, synth):
+    rows = []
+    for name in SWEEP:
+        r = run_workload(name, args.steps, args.warmup, torch, asp, synth, False)
+        roof = r["roofline"]
+        rows.append({"workload": name, "b_row": r["b_row"], "N": r["N"], "nnz": r["nnz"], "bn": r["bn"],
+                     "kernel_ms": roof["kernel_ms_avg"], "effective_gflops": r["value"], "bound": roof["bound"],
+                     "achieved": roof["achieved"], "unit": roof["unit"], "frac": roof["frac"],
+                     "algorithmic_bytes": r["algorithmic_bytes"], "convert_s": r["convert_s"]})
+        print("sweep", name, "%.4f ms" % roof["kernel_ms_avg"], "%.1f %s" % (roof["achieved"], roof["unit"]),
+              file=sys.stderr, flush=True)
+    print(json.dumps({"sweep": rows, "steps": args.steps, "warmup": args.warmup}))
+
+
 def box_peaks(torch, asp):
     """What this machine sustains, beside the published peaks: matrix-core rate of an MFMA-only loop (both dtypes) and
     the bandwidth of a plain 1 GiB device copy (read + write), of a 1 GiB fill (write only) and of a read-only stream over 1 GiB."""
@@ -291,6 +323,9 @@ def main():
                          "which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
     ap.add_argument("--mlp-chain", action="store_true",
                     help="time gate, up and down projections of the feed-forward block chained through asp_spmm_xt")
+    ap.add_argument("--sweep", action="store_true",
+                    help="the long-prefill BCSR grid (block sizes x sparsities) and the band + long rows WCSR workload at "
+                         "both widths: one JSON object, no CPU baseline")
     ap.add_argument("--ablation", action="store_true",
                     help="run the BCSR workload once per kernel variant (child processes) and print one JSON object")
     args = ap.parse_args()
@@ -323,6 +358,9 @@ def main():
     asp.lib()  # raises when the HIP library has not been built
     if args.mlp_chain:
         run_mlp_chain(args, torch, synth)
+        return
+    if args.sweep:
+        run_sweep(args, torch, asp, synth)
         return
 
     main_res = run_workload(args.workload, args.steps, args.warmup, torch, asp, synth, not args.no_cpu_baseline)

@@ -28,6 +28,9 @@ static void free_device(asp_handle *h) {
     (void)hipFree(h->d_rank_info);
     (void)hipFree(h->d_ws_slot);
     (void)hipFree(h->d_ws);
+    (void)hipFree(h->d_c_rank_info);
+    (void)hipFree(h->d_c_slice_rows);
+    (void)hipFree(h->d_c_values);
     if (cur >= 0 && cur != h->device) (void)hipSetDevice(cur);
 }
 
@@ -58,6 +61,27 @@ static asp_status_t create_impl(const asp_config_t *cfg, int64_t m, int64_t k, i
         h->task_cols = 0;
         csr_to_bcsr(m, k, row_ptr, col_idx, values, es, cfg->b_row, cfg->b_col, h->hb);
         h->n_units = (int64_t)h->hb.block_col_idx.size();
+        // Smaller blocks: the kernel for 128-row tiles on the composite form (asp_convert.cpp) beats the small-block
+        // kernel, which reads twice / four times the LDS bytes per MFMA, until the zero fill outweighs that.
+        // Measured on 8192 x 8192 matrices with geometric block-row lengths (N = 65536) at 50 / 75 / 90 / 95 / 99 %
+        // block sparsity: 64x64 blocks, fill 1.46 / 1.78 / 1.96 / 2.01 / 2.43 -> 1.54 / 1.39 / 1.27 / 1.23 / 1.10
+        // times faster; 32x32 blocks, fill 2.14 / 2.74 / 3.51 / 3.86 / 4.51 -> 1.85 / 1.64 / 1.19 / 1.15 / 0.99.
+        // ASP_BCSR_COMPOSITE=0/1 is a benchmarking switch.
+        if (cfg->dtype == ASP_DT_BF16 && cfg->b_row < 128 && k % cfg->b_row == 0 && h->n_units > 0) {
+            static const int env_comp = [] {
+                const char *e = std::getenv("ASP_BCSR_COMPOSITE");
+                return e ? std::atoi(e) : -1;
+            }();
+            if (env_comp != 0) {
+                h->comp_inflation = bcsr_build_composite(h->hb, m, cfg->b_row, h->hc);
+                const double limit = cfg->b_row == 64 ? 2.6 : 4.3;
+                h->has_comp = env_comp == 1 || h->comp_inflation <= limit;
+                h->c_n_brows = (int64_t)h->hc.block_row_ptr.size() - 1;
+                h->c_n_units = (int64_t)h->hc.block_col_idx.size();
+                if (!h->has_comp || host_only) h->hc.packed = std::vector<uint8_t>();
+                if (!h->has_comp) h->hc = HostBcsr();
+            }
+        }
         if (host_only) return ASP_OK;
         if (cfg->dtype == ASP_DT_F32)
             bcsr_pack_fragments_f32(h->hb, cfg->b_row, cfg->b_col, h->hb.packed);
@@ -71,8 +95,14 @@ static asp_status_t create_impl(const asp_config_t *cfg, int64_t m, int64_t k, i
         ASP_HIP_TRY(hipDeviceGetAttribute(&h->n_cus, hipDeviceAttributeMultiprocessorCount, h->device));
         bcsr_build_schedule(h->hb);
         if ((s = upload(&h->d_rank_info, h->hb.rank_info.data(), h->hb.rank_info.size() * 4, stream))) return s;
+        if (h->has_comp) {
+            if ((s = upload(&h->d_c_rank_info, h->hc.rank_info.data(), h->hc.rank_info.size() * 4, stream))) return s;
+            if ((s = upload(&h->d_c_slice_rows, h->hc.slice_rows.data(), h->hc.slice_rows.size() * 4, stream))) return s;
+            if ((s = upload(&h->d_c_values, h->hc.packed.data(), h->hc.packed.size(), stream))) return s;
+        }
         ASP_HIP_TRY(hipStreamSynchronize(stream));
         std::vector<uint8_t>().swap(h->hb.packed);  // the device copy is the only user
+        std::vector<uint8_t>().swap(h->hc.packed);
         return ASP_OK;
     }
 

@@ -75,7 +75,12 @@ struct WideCfg {
 //   a token XOR-swizzled by (token / 4) % 4) and read with plain 16-byte reads (it already is k-contiguous);
 //   the MFMA operands are not swapped, so a lane ends with 4 adjacent outputs of one token; the epilogue
 //   transposes 32 tokens x 128 outputs at a time and stores 256-byte row segments of Y.
-template <bool KAL, bool XT>
+//
+// GATHER = true: the composite form of a matrix with 64x64 or 32x32 blocks (asp_convert.cpp): a "block" is 128 rows
+// x four 32-wide K slices that multiply four separately placed 32-row strips of the dense operand;
+// block_col_idx then holds, per block, the first dense row of each slice (int4) instead of a block column.
+// Needs KAL (every strip lies inside K).
+template <bool KAL, bool XT, bool GATHER>
 __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     const int4 *__restrict__ rank_info, const int32_t *__restrict__ block_col_idx,
     const uint16_t *__restrict__ a_packed, const uint16_t *__restrict__ B, uint16_t *__restrict__ C, int M, int K,
@@ -175,7 +180,13 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     int c_br = 0, c_n0 = 0, c_nb = 0;                                   // tile being multiplied (nb: blocks)
     int n_br = 0, n_n0 = 0, n_nb = 0, n_blk0 = 0, n_bcol0 = 0, have_next = 0;  // the tile after it
     uint32_t n_col = 0;  // byte offset of this lane's 16-byte chunk inside a row of B
-    auto decode = [&](int idx, int &br, int &n0, int &nb, int &blk0, int &bcol0, uint32_t &colb) __attribute__((always_inline)) {
+    int4 n_srow = {0, 0, 0, 0};  // GATHER: dense rows of the four slices of the tile's first block
+    static_assert(!GATHER || KAL, "the composite form keeps every strip inside K");
+    auto uniform4 = [&](int4 v) __attribute__((always_inline)) {
+        return int4{__builtin_amdgcn_readfirstlane(v.x), __builtin_amdgcn_readfirstlane(v.y),
+                    __builtin_amdgcn_readfirstlane(v.z), __builtin_amdgcn_readfirstlane(v.w)};
+    };
+    auto decode = [&](int idx, int &br, int &n0, int &nb, int &blk0, int &bcol0, uint32_t &colb, int4 &srow) __attribute__((always_inline)) {
         const int per_group = group_n * n_rows;
         const int grp = idx / per_group, in_grp = idx - grp * per_group;
         const int left = n_tiles - grp * group_n;
@@ -189,6 +200,7 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
         blk0 = __builtin_amdgcn_readfirstlane(ri.y);
         nb = __builtin_amdgcn_readfirstlane(ri.z);
         bcol0 = __builtin_amdgcn_readfirstlane(ri.w);
+        if (GATHER) srow = uniform4(((const int4 *)block_col_idx)[blk0]);
         n0 = nt * BN;
         int col = n0 + 8 * b_chunk;
         col = col < N ? col : N - 8;  // chunks past N only feed columns that are never stored
@@ -201,6 +213,8 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     int pf_nb = 0, pf_b = 0, pf_blk = 0, pf_in_next = 0;
     int pf_bcol = 0;      // block column of block pf_blk
     int pf_bcol_ld = 0;   // block column of stored block pf_blk + 1 (loaded one block early)
+    int4 pf_srow = {0, 0, 0, 0}, pf_srow_ld = {0, 0, 0, 0};  // GATHER: the same for the slices' dense rows
+    const uint8_t *pf_bb1 = nullptr, *pf_bb2 = nullptr, *pf_bb3 = nullptr;  // GATHER: dense operand of slices 1..3
     uint32_t pf_voff[Cfg::B_LPW];     // per-lane byte offsets of the 8 rows this wave loads of a slice of B
     const uint8_t *pf_abase = nullptr; // next A slice to request
     const uint8_t *pf_bbase = nullptr; // first row of B of the next slice to request
@@ -230,25 +244,39 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
         // register only five wait states after a vector instruction wrote it, the compiler keeps such
         // wave-uniform values in vector registers at times, and it does not see the loads inside the asm)
         pf_abase = (const uint8_t *)uniform_ptr((const uint8_t *)a_packed + (int64_t)pf_blk * (BR * BR * 2));
+        int nb_ = pf_blk + 1;
+        nb_ = nb_ < n_blocks ? nb_ : n_blocks - 1;
+        if (GATHER) {
+            const uint8_t *origin = XT ? (const uint8_t *)B + (int64_t)pf_n0 * row_bytes : (const uint8_t *)B;
+            const int64_t unit = XT ? 2 : row_bytes;  // one dense row (XT: one k) further
+            pf_bbase = (const uint8_t *)uniform_ptr(origin + (int64_t)pf_srow.x * unit);
+            pf_bb1 = (const uint8_t *)uniform_ptr(origin + (int64_t)pf_srow.y * unit);
+            pf_bb2 = (const uint8_t *)uniform_ptr(origin + (int64_t)pf_srow.z * unit);
+            pf_bb3 = (const uint8_t *)uniform_ptr(origin + (int64_t)pf_srow.w * unit);
+            pf_srow_ld = uniform4(((const int4 *)block_col_idx)[nb_]);
+            return;
+        }
         pf_bbase = (const uint8_t *)uniform_ptr(
             XT ? (const uint8_t *)B + (int64_t)pf_n0 * row_bytes + (int64_t)pf_bcol * BR * 2
                : (const uint8_t *)B + (int64_t)pf_bcol * BR * row_bytes);
-        int nb_ = pf_blk + 1;
-        nb_ = nb_ < n_blocks ? nb_ : n_blocks - 1;
         pf_bcol_ld = __builtin_amdgcn_readfirstlane(block_col_idx[nb_]);
     };
+    // dense operand of slice s_ of the cursor's block, s_ a compile-time constant in 1..3
+    auto gather_base = [&](int s_) __attribute__((always_inline)) { return s_ == 1 ? pf_bb1 : s_ == 2 ? pf_bb2 : pf_bb3; };
     // once per block, before its slice 0 is requested
     auto cursor_next_block = [&]() __attribute__((always_inline)) {
         ++pf_b;
         if (pf_b < pf_nb) {
             ++pf_blk;
             pf_bcol = pf_bcol_ld;
+            pf_srow = pf_srow_ld;
         } else if (have_next && !pf_in_next) {
             pf_in_next = 1;
             pf_nb = n_nb;
             pf_b = 0;
             pf_blk = n_blk0;
             pf_bcol = n_bcol0;
+            pf_srow = n_srow;
             cursor_set_tile(n_col);
         } else {
             pf_b = pf_nb - 1;  // end of the stream: the same block again
@@ -412,7 +440,8 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
         ASP_FENCE();                                                                                               \
         ASP_PHASE(f1, f0, nb_, 0, ASP_RQ_B3, ASP_RQ_B4, ASP_RQ_B5, ASP_RQ_B6, ASP_RQ_B7, (void)0);                 \
         pf_abase = (const uint8_t *)uniform_ptr(pf_abase + Cfg::A_STAGE);                                          \
-        pf_bbase = (const uint8_t *)uniform_ptr(pf_bbase + slice_step);                                            \
+        if (GATHER) { if (rs_ < NS - 1) pf_bbase = gather_base(rs_ + 1); }                                         \
+        else pf_bbase = (const uint8_t *)uniform_ptr(pf_bbase + slice_step);                                       \
         if (HI_POSSIBLE) vm_hi = vm_hi > 0 ? vm_hi - 1 : 0;                                                        \
         ASP_FENCE();                                                                                               \
     } while (0)
@@ -421,7 +450,7 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     {
         int blk0, bcol0;
         uint32_t colb;
-        decode(idx_cur, c_br, c_n0, c_nb, blk0, bcol0, colb);
+        decode(idx_cur, c_br, c_n0, c_nb, blk0, bcol0, colb, pf_srow);
         pf_nb = c_nb;
         pf_blk = blk0;
         pf_bcol = bcol0;
@@ -429,7 +458,7 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
         cursor_set_block();
         if (tile_of_round(1) < run_end) {
             have_next = 1;
-            decode(tile_of_round(1), n_br, n_n0, n_nb, n_blk0, n_bcol0, n_col);
+            decode(tile_of_round(1), n_br, n_n0, n_nb, n_blk0, n_bcol0, n_col, n_srow);
         }
     }
 #pragma unroll
@@ -447,7 +476,8 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
         for (int i = 0; i < Cfg::B_LPW; ++i)
             dma16_to_lds(ASP_B_BASE(s), ASP_B_VOFF(s, i), m0_base + s * Cfg::STAGE + Cfg::A_STAGE + i * NW * 1024);
         pf_abase += Cfg::A_STAGE;
-        pf_bbase += slice_step;
+        if (GATHER) pf_bbase = gather_base(s + 1);
+        else pf_bbase += slice_step;
     }
     wait_vmcnt_and_lds<2 * Cfg::LPW>();
     barrier_no_fence();
@@ -471,7 +501,8 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
         const int idx_nn = tile_of_round(round + 2);
         int nn_br = 0, nn_n0 = 0, nn_nb = 0, nn_blk0 = 0, nn_bcol0 = 0;
         uint32_t nn_col = 0;
-        if (idx_nn < run_end) decode(idx_nn, nn_br, nn_n0, nn_nb, nn_blk0, nn_bcol0, nn_col);
+        int4 nn_srow = {0, 0, 0, 0};
+        if (idx_nn < run_end) decode(idx_nn, nn_br, nn_n0, nn_nb, nn_blk0, nn_bcol0, nn_col, nn_srow);
 
         // the buffer of the slice just finished (always the last one of the ring) is the spare one
         // until the next barrier
@@ -544,6 +575,7 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
             n_blk0 = nn_blk0;
             n_bcol0 = nn_bcol0;
             n_col = nn_col;
+            n_srow = nn_srow;
             have_next = 1;
         } else {
             have_next = 0;
@@ -575,6 +607,25 @@ __global__ __launch_bounds__(256) void bcsr_clear_empty_rows_kernel(const int4 *
     for (int64_t i = (int64_t)blockIdx.y * 256 + threadIdx.x; i < n16; i += (int64_t)gridDim.y * 256) dst[i] = z;
 }
 
+// What the kernel walks: the handle's own 128x128 blocks, or the composite form of a handle with smaller blocks.
+struct WideOperand {
+    const int4 *rank_info;
+    const int32_t *cols;  // block columns, or (composite) four dense rows per block
+    const uint16_t *values;
+    const std::vector<int64_t> *weight_prefix;
+    int64_t n_rows, n_brows, n_blocks;  // non-empty block-rows, all block-rows, blocks
+    bool composite;
+};
+static WideOperand wide_operand(const asp_handle *h) {
+    if (h->b_row == 128)
+        return WideOperand{(const int4 *)h->d_rank_info, h->d_col_idx,          (const uint16_t *)h->d_values,
+                           &h->hb.sorted_weight_prefix,  h->hb.n_nonempty,      h->n_brows,
+                           h->n_units,                   false};
+    return WideOperand{(const int4 *)h->d_c_rank_info, h->d_c_slice_rows,     (const uint16_t *)h->d_c_values,
+                       &h->hc.sorted_weight_prefix,    h->hc.n_nonempty,      h->c_n_brows,
+                       h->c_n_units,                   true};
+}
+
 template <bool XT>
 static void launch_wide(const asp_handle *h, const void *B, void *C, int64_t N, int n_tiles, hipStream_t stream) {
     static const int env_group = [] {  // benchmarking switch only
@@ -585,7 +636,8 @@ static void launch_wide(const asp_handle *h, const void *B, void *C, int64_t N, 
     // still has a chance in the 4 MB of L2 (measured: 1, 3 and 4 are 3-10 % slower on the 90 %-sparse projection)
     int group_n = env_group > 0 ? env_group : 2;
     if (group_n > n_tiles) group_n = n_tiles;
-    const int64_t n_rows = h->hb.n_nonempty;
+    const WideOperand op = wide_operand(h);
+    const int64_t n_rows = op.n_rows;
     int64_t workers = h->n_cus;  // one resident workgroup per CU: the ring takes the whole LDS
     if (workers > n_rows * n_tiles) workers = n_rows * n_tiles;
     workers = std::max<int64_t>(8, workers / 8 * 8);  // the same number of workgroups on every XCD
@@ -593,27 +645,29 @@ static void launch_wide(const asp_handle *h, const void *B, void *C, int64_t N, 
         const char *e = std::getenv("ASP_BCSR_XCD_AWARE");
         return e ? std::atoi(e) : 1;
     }();
-    XcdRuns runs = cut_runs(h->hb.sorted_weight_prefix, n_rows, n_tiles, group_n);
+    XcdRuns runs = cut_runs(*op.weight_prefix, n_rows, n_tiles, group_n);
     if (!env_xcd)
         for (int x = 1; x <= 8; ++x) runs.start[x] = runs.start[8];
     dim3 grid((unsigned)workers), block(256);
-    if (h->k % 128 == 0)
-        hipLaunchKernelGGL((bcsr_spmm_wide_kernel<true, XT>), grid, block, 0, stream, (const int4 *)h->d_rank_info,
-                           h->d_col_idx, (const uint16_t *)h->d_values, (const uint16_t *)B, (uint16_t *)C, (int)h->m,
-                           (int)h->k, (int)N, (int)n_rows, (int)h->n_brows, (int)h->n_units, n_tiles, group_n, env_xcd, runs);
-    else
-        hipLaunchKernelGGL((bcsr_spmm_wide_kernel<false, XT>), grid, block, 0, stream, (const int4 *)h->d_rank_info,
-                           h->d_col_idx, (const uint16_t *)h->d_values, (const uint16_t *)B, (uint16_t *)C, (int)h->m,
-                           (int)h->k, (int)N, (int)n_rows, (int)h->n_brows, (int)h->n_units, n_tiles, group_n, env_xcd, runs);
+#define ASP_LAUNCH_WIDE(KAL, GATHER)                                                                                   \
+    hipLaunchKernelGGL((bcsr_spmm_wide_kernel<KAL, XT, GATHER>), grid, block, 0, stream, op.rank_info, op.cols, op.values, \
+                       (const uint16_t *)B, (uint16_t *)C, (int)h->m, (int)h->k, (int)N, (int)n_rows, (int)op.n_brows,  \
+                       (int)op.n_blocks, n_tiles, group_n, env_xcd, runs)
+    if (op.composite) ASP_LAUNCH_WIDE(true, true);  // built only for K % block size == 0
+    else if (h->k % 128 == 0) ASP_LAUNCH_WIDE(true, false);
+    else ASP_LAUNCH_WIDE(false, false);
+#undef ASP_LAUNCH_WIDE
 }
 
-// needs b_row = 128, bn = 512, N % 8 == 0, 8 <= N < 2^25 and 16-byte aligned B and C (the caller checked)
+// needs 128x128 blocks or the composite form, bn = 512, N % 8 == 0, 8 <= N < 2^25 and 16-byte aligned B and C
+// (the caller checked)
 bool bcsr_wide_launch(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream) {
-    if (h->b_row != 128 || p.bn != 512) return false;
-    const int64_t n_rows = h->hb.n_nonempty, n_empty = h->n_brows - n_rows;
+    if ((h->b_row != 128 && !h->has_comp) || p.bn != 512) return false;
+    const WideOperand op = wide_operand(h);
+    const int64_t n_rows = op.n_rows, n_empty = op.n_brows - n_rows;
     if (n_empty > 0 && n_rows == 0) {  // nothing to multiply: the clearing is all there is
         dim3 grid((unsigned)n_empty, 16), block(256);
-        hipLaunchKernelGGL(bcsr_clear_empty_rows_kernel, grid, block, 0, stream, (const int4 *)h->d_rank_info, (int)n_rows,
+        hipLaunchKernelGGL(bcsr_clear_empty_rows_kernel, grid, block, 0, stream, op.rank_info, (int)n_rows,
                            (uint16_t *)C, (int)h->m, (int)N, 128);
     }
     if (n_rows == 0) return true;
@@ -671,7 +725,8 @@ __global__ __launch_bounds__(256) void bcsr_fill_zero_kernel(uint16_t *__restric
 }
 
 asp_status_t bcsr_spmm_xt_launch(const asp_handle *h, const void *X, void *Y, int64_t N, hipStream_t stream) {
-    const int64_t n_rows = h->hb.n_nonempty;
+    const bool wide_ok = h->b_row == 128 || h->has_comp;
+    const int64_t n_rows = h->b_row == 128 || !h->has_comp ? h->hb.n_nonempty : h->hc.n_nonempty;
     if (n_rows == 0) {
         hipLaunchKernelGGL(bcsr_fill_zero_kernel, dim3(1024), dim3(256), 0, stream, (uint16_t *)Y, N * h->m);
     } else {
@@ -683,7 +738,7 @@ asp_status_t bcsr_spmm_xt_launch(const asp_handle *h, const void *X, void *Y, in
             const char *e = std::getenv("ASP_BCSR_XT");
             return e && std::strcmp(e, "generic") == 0;
         }();
-        if (!force_generic && h->b_row == 128 && aligned && h->k % 8 == 0 && h->m % 8 == 0 && N < (1ll << 25) &&
+        if (!force_generic && wide_ok && aligned && h->k % 8 == 0 && h->m % 8 == 0 && N < (1ll << 25) &&
             h->k < (1ll << 22) && n_rows * n_tiles >= cus) {
             launch_wide<true>(h, X, Y, N, (int)n_tiles, stream);
         } else {

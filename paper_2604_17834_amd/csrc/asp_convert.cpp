@@ -197,6 +197,71 @@ void bcsr_build_schedule(HostBcsr &b) {
     }
 }
 
+// Composite form of a bf16 BCSR matrix with 64x64 or 32x32 blocks, for the kernel written for 128x128 blocks
+// (Section II-C's block product, regrouped): R = 128 / b vertically adjacent block-rows make one 128-row
+// super-row; the union of their block columns is cut into groups of R; a composite block holds, for each of its
+// R columns j, the b-wide column strip [block(r0, j); ...; block(r0 + R - 1, j)] (zeros where a block is not
+// stored) as b / 32 consecutive 32-wide K slices.  slice_rows gives, per composite block, the first row of B that
+// each of its four K slices multiplies (for a plain 128x128 block these would be 128 J + 0, 32, 64, 96).
+// Strips that pad the last group are zeros and repeat the rows of the last real strip.
+// Returns the work inflation: composite blocks x 128 x 128 over stored blocks x b x b.
+double bcsr_build_composite(const HostBcsr &in, int64_t m, int32_t b, HostBcsr &out) {
+    const int64_t nbr = (int64_t)in.block_row_ptr.size() - 1;
+    const int32_t R = 128 / b, spv = b / 32;  // strips per composite block; K slices per strip
+    const int64_t nsr = ceil_div(m, 128);
+    out = HostBcsr();
+    out.block_row_ptr.assign(nsr + 1, 0);
+    std::vector<std::vector<int32_t>> uni((size_t)nsr);
+    parallel_chunks(nsr, 16, [&](unsigned, int64_t lo, int64_t hi) {
+        for (int64_t sr = lo; sr < hi; ++sr) {
+            auto &u = uni[sr];
+            const int64_t r0 = sr * R, r1 = std::min<int64_t>(nbr, r0 + R);
+            u.assign(in.block_col_idx.begin() + in.block_row_ptr[r0], in.block_col_idx.begin() + in.block_row_ptr[r1]);
+            std::sort(u.begin(), u.end());
+            u.erase(std::unique(u.begin(), u.end()), u.end());
+            out.block_row_ptr[sr + 1] = (int32_t)ceil_div((int64_t)u.size(), R);
+        }
+    });
+    for (int64_t sr = 0; sr < nsr; ++sr) out.block_row_ptr[sr + 1] += out.block_row_ptr[sr];
+    const int64_t nc = out.block_row_ptr[nsr];
+    out.block_col_idx.assign(nc, 0);
+    out.slice_rows.assign((size_t)nc * 4, 0);
+    out.blocks.assign((size_t)nc * 128 * 128 * 2, 0);
+    const uint16_t *src = (const uint16_t *)in.blocks.data();
+    uint16_t *dst = (uint16_t *)out.blocks.data();
+    parallel_chunks(nsr, 4, [&](unsigned, int64_t lo, int64_t hi) {
+        for (int64_t sr = lo; sr < hi; ++sr) {
+            const auto &u = uni[sr];
+            const int64_t r0 = sr * R, r1 = std::min<int64_t>(nbr, r0 + R);
+            for (int64_t c = out.block_row_ptr[sr]; c < out.block_row_ptr[sr + 1]; ++c) {
+                const int64_t first = (c - out.block_row_ptr[sr]) * R;
+                for (int32_t v = 0; v < R; ++v) {
+                    const bool real = first + v < (int64_t)u.size();
+                    const int32_t j = u[real ? first + v : u.size() - 1];
+                    for (int32_t t = 0; t < spv; ++t) out.slice_rows[4 * c + v * spv + t] = j * b + 32 * t;
+                    if (!real) continue;
+                    for (int64_t br = r0; br < r1; ++br) {
+                        const int32_t *cb = in.block_col_idx.data() + in.block_row_ptr[br];
+                        const int32_t *ce = in.block_col_idx.data() + in.block_row_ptr[br + 1];
+                        const int32_t *hit = std::lower_bound(cb, ce, j);
+                        if (hit == ce || *hit != j) continue;
+                        const uint16_t *sb = src + (int64_t)(hit - in.block_col_idx.data()) * b * b;
+                        for (int32_t r = 0; r < b; ++r)
+                            std::memcpy(dst + c * 128 * 128 + ((br - r0) * b + r) * 128 + v * b, sb + (int64_t)r * b,
+                                        (size_t)b * 2);
+                    }
+                }
+                out.block_col_idx[c] = out.slice_rows[4 * c] / 128;  // the schedule orders block-rows by this
+            }
+        }
+    });
+    bcsr_build_schedule(out);
+    bcsr_pack_fragments_bf16(out, 128, 128, out.packed);
+    out.blocks = std::vector<uint8_t>();  // only the packed form is used
+    const double stored = (double)in.block_col_idx.size() * b * b;
+    return stored > 0 ? (double)nc * 128 * 128 / stored : 0.0;
+}
+
 // Kernel-internal order of a bf16 block: for each 16-wide k slice, for each group of 32 rows, the 64
 // lanes of a wavefront hold 8 consecutive k each (lane l: row l % 32, k offset 8 * (l / 32)), which
 // is the A/B operand layout of v_mfma_f32_32x32x16_bf16.  A pure permutation of the canonical block.

@@ -73,6 +73,7 @@ struct HostBcsr {
     std::vector<int32_t> rank_info;            // [n_brows][4]
     std::vector<int64_t> sorted_weight_prefix; // [n_brows + 1]
     int64_t n_nonempty = 0;                    // block-rows with at least one stored block (they come first)
+    std::vector<int32_t> slice_rows;           // composite form only: [blocks][4] first row of B of each K slice
 };
 
 struct HostWcsr {
@@ -88,6 +89,7 @@ struct HostWcsr {
 void csr_to_bcsr(int64_t m, int64_t k, const int32_t *row_ptr, const int32_t *col_idx, const void *values,
                  size_t esize, int32_t b_row, int32_t b_col, HostBcsr &out);
 void bcsr_build_schedule(HostBcsr &b);
+double bcsr_build_composite(const HostBcsr &in, int64_t m, int32_t b, HostBcsr &out);
 void bcsr_pack_fragments_bf16(const HostBcsr &in, int32_t b_row, int32_t b_col, std::vector<uint8_t> &packed);
 void bcsr_pack_fragments_f32(const HostBcsr &in, int32_t b_row, int32_t b_col, std::vector<uint8_t> &packed);
 bool csr_to_wcsr(int64_t m, int64_t k, const int32_t *row_ptr, const int32_t *col_idx, const void *values,
@@ -111,6 +113,15 @@ struct asp_handle {
     int64_t n_split_tasks = 0;    // WCSR: tasks of those windows = scratch slots
 
     asp::HostBcsr hb;  // BCSR: canonical arrays stay on the host for export
+    // bf16 BCSR with 64x64 / 32x32 blocks: the composite form (128-row super-rows, asp_convert.cpp) when it was
+    // judged worth it at creation; hc keeps its scheduling data, the packed values live on the device only
+    asp::HostBcsr hc;
+    bool has_comp = false;
+    double comp_inflation = 0.0;    // composite work over stored-block work
+    int64_t c_n_brows = 0, c_n_units = 0;  // super-rows, composite blocks
+    int32_t *d_c_rank_info = nullptr;
+    int32_t *d_c_slice_rows = nullptr;     // [composite blocks][4]
+    void *d_c_values = nullptr;
     asp::HostWcsr hw;  // WCSR: kept only in host-convert mode (device arrays are canonical)
 
     // device arrays

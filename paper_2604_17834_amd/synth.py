@@ -14,6 +14,7 @@ weights (LLM case study, Section IV-D) and irregular SuiteSparse-like matrices
 """
 from __future__ import annotations
 
+import re
 from dataclasses import dataclass
 
 import numpy as np
@@ -243,6 +244,20 @@ def workload(name: str, scale: float = 1.0):
     for suffix, d in (("_f32", F32), ("_bf16", BF16)):
         if name.endswith(suffix):
             name, dt = name[:-len(suffix)], d
+    n_override = None   # "_n<width>": the same matrix against a dense operand of another width
+    mm = re.match(r"^(.*)_n(\d+)$", name)
+    if mm:
+        name, n_override = mm.group(1), int(mm.group(2))
+    if n_override is not None:
+        w = list(workload(name + ("_" + dt if dt else ""), scale))
+        w[4] = n_override
+        return tuple(w)
+    mm = re.match(r"^bcsr_sweep_b(32|64|128)_s(\d+)$", name)
+    if mm:                              # config 5: long prefill, geometric block-row lengths
+        b, pct = int(mm.group(1)), int(mm.group(2))
+        m = max(4 * b, int(8192 * s))
+        a = block_sparse_geometric(m, m, b, b, pct / 100.0, seed=1030 + b + pct, dtype=dt or BF16)
+        return a, "bcsr", b, b, max(256, int(65536 * s)), dt or BF16, 1008
     blk = 128   # "_b64" / "_b32": the config-2 shapes pruned in smaller square blocks (same sparsity, own mask)
     for suffix, b in (("_b64", 64), ("_b32", 32)):
         if name.endswith(suffix) and name.startswith("bcsr_") and name != "bcsr_small" + suffix:

@@ -240,6 +240,88 @@ def test_bcsr_wide_tiles_times_identity_is_A_bit_exact():
     assert np.array_equal(C, dense)
 
 
+# ---- 64 x 64 and 32 x 32 blocks through the composite form (128-row super-rows, four gathered K slices per block) --
+def _plan_bn_b(a, b, N):
+    h = asp.asp_create_from_csr("bcsr", "bf16", b, b, a.m, a.k, a.row_ptr, a.col_idx, a.values)
+    try:
+        return asp.asp_plan_spmm(h, N).bn
+    finally:
+        asp.asp_destroy(h)
+
+
+@pytest.mark.parametrize("b", [64, 32])
+@pytest.mark.parametrize("m,k,N,sparsity,geometric", [
+    (2048, 1024, 8192, 0.5, True),          # aligned everywhere
+    (2048 - 40, 1024, 8192 + 72, 0.5, True),  # last block-row and last super-row ragged, N tail
+    (4096, 2048, 4096, 0.3, False),         # dense-ish Bernoulli mask: nearly every strip is full
+    (4096, 512, 4096 - 8, 0.6, False),
+])
+def test_bcsr_small_blocks_composite_parity(b, m, k, N, sparsity, geometric):
+    k = k + b                                # a multiple of the block size but not of 128
+    gen = synth.block_sparse_geometric if geometric else synth.block_sparse_bernoulli
+    a = gen(m, k, b, b, sparsity, seed=61 + b, dtype="bf16")
+    assert _plan_bn_b(a, b, N) == 512        # the composite form is in use
+    B = synth.dense_normal(k, N, "bf16", seed=62)
+    C = gpu_spmm(a, "bcsr", b, b, B)
+    cols = np.r_[0:64, N // 2 - 32:N // 2 + 32, N - 64:N]
+    check_against_oracle(a, B, C, cols)
+
+
+@pytest.mark.parametrize("b", [64, 32])
+def test_bcsr_small_blocks_composite_empty_rows_rerun_and_identity(b):
+    m, k = 6144, 4096
+    a = synth.block_sparse_bernoulli(m, k, b, b, 0.5, seed=63 + b, dtype="bf16")
+    # empty out block-rows: single ones inside a super-row and two whole super-rows (rows 512..767)
+    keep = np.ones(a.nnz, dtype=bool)
+    rows = np.repeat(np.arange(a.m), np.diff(a.row_ptr))
+    keep[((rows // b) % 7 == 3) | ((rows >= 512) & (rows < 768))] = False
+    rp = np.zeros(a.m + 1, dtype=np.int64)
+    np.add.at(rp, rows[keep] + 1, 1)
+    a2 = synth.Csr(a.m, a.k, np.cumsum(rp).astype(np.int32), a.col_idx[keep], a.values[keep], a.dtype)
+    N = k
+    assert _plan_bn_b(a2, b, N) == 512
+    I = synth.dense_identity(k, "bf16")
+    C1 = gpu_spmm(a2, "bcsr", b, b, I)
+    C2 = gpu_spmm(a2, "bcsr", b, b, I)
+    assert np.array_equal(C1, C2)
+    dense = np.zeros((m, k), dtype=np.uint16)
+    dense[rows[keep], a2.col_idx] = a2.values
+    dense[dense == 0x8000] = 0  # a stored -0.0 times 1.0, added to the +0.0 the sum starts from, is +0.0
+    assert np.array_equal(C1, dense)
+    assert not C1[512:768].any()
+
+
+@pytest.mark.parametrize("b", [64, 32])
+def test_bcsr_small_blocks_composite_equals_small_block_kernel_within_rounding(b):
+    # the same handle on a width where the composite form is not used (too few tiles) gives the same columns up
+    # to the order of the fp32 sums: both must sit inside the oracle's bound, and mostly agree bit for bit
+    a = synth.block_sparse_geometric(2048, 2048, b, b, 0.5, seed=65 + b, dtype="bf16")
+    B = synth.dense_normal(a.k, 8192, "bf16", seed=66)
+    h = asp.asp_create_from_csr("bcsr", "bf16", b, b, a.m, a.k, a.row_ptr, a.col_idx, a.values)
+    try:
+        assert asp.asp_plan_spmm(h, 8192).bn == 512 and asp.asp_plan_spmm(h, 256).bn == 256
+        Cw = gpu_spmm(a, "bcsr", b, b, B, handle=h)
+        Cn = gpu_spmm(a, "bcsr", b, b, np.ascontiguousarray(B[:, 1024:1280]), handle=h)
+    finally:
+        asp.asp_destroy(h)
+    check_against_oracle(a, np.ascontiguousarray(B[:, 1024:1280]), Cn)
+    check_against_oracle(a, np.ascontiguousarray(B[:, 1024:1280]), Cw[:, 1024:1280])
+    assert (Cw[:, 1024:1280] == Cn).mean() > 0.9
+
+
+@pytest.mark.parametrize("b", [64, 32])
+def test_bcsr_xt_small_blocks_composite_parity(b):
+    m, k, N = 2048, 1024 + b, 8192 + 40
+    a = synth.block_sparse_geometric(m, k, b, b, 0.5, seed=67 + b, dtype="bf16")
+    X = synth.dense_normal(N, k, "bf16", seed=68)
+    Y = gpu_spmm_xt(a, b, X)
+    tok = np.r_[0:48, 4000:4048, N - 48:N]
+    check_against_oracle(a, np.ascontiguousarray(X[tok].T), np.ascontiguousarray(Y[tok].T))
+    # bit for bit the product of the transposed operands through asp_spmm (both take the composite path)
+    C = gpu_spmm(a, "bcsr", b, b, np.ascontiguousarray(X.T))
+    assert np.array_equal(Y, C.T)
+
+
 # ---- K-contiguous entry: Y[N x m] = X[N x k] x A^T (Section IV-D's layout) -----------------------------------
 def gpu_spmm_xt(a: synth.Csr, b, X: np.ndarray, misalign=False):
     h = asp.asp_create_from_csr("bcsr", a.dtype, b, b, a.m, a.k, a.row_ptr, a.col_idx, a.values)
