@@ -93,7 +93,8 @@ typedef struct {
 typedef enum { ASP_ARR_ROW_PTR = 0, ASP_ARR_COL_IDX = 1, ASP_ARR_VALUES = 2, ASP_ARR_TASKS = 3 } asp_array_t;
 
 /* How asp_spmm would run for a dense width N (Section IV-C: tile-width selection).  bf16 BCSR picks, among its
- * tile widths 64 / 128 / 256 / 512 (512: 128x128 blocks with at least one tile per compute unit), the one with the
+ * tile widths 64 / 128 / 256 / 512 (512: tiles of 128 rows -- 128x128 blocks, or 128-row stacks of smaller blocks where
+ * the handle keeps them -- with at least one tile per compute unit), the one with the
  * least padded width x cost per column, costs 118 / 89 / 71 / 64 (ties: the wider); fp32 BCSR and WCSR take the
  * widest of their widths that divides N, else the one that pads least. */
 typedef struct {
@@ -150,8 +151,10 @@ asp_status_t asp_reserve(asp_handle_t *h, int64_t N);
  * X: DEVICE, N x k row-major (leading dimension k).  Y: DEVICE, N x m row-major (leading dimension m), fully
  * overwritten; Y must not alias X.  1 <= N <= ASP_MAX_N.  BCSR handles (bf16) only; others return ASP_ERR_UNSUPPORTED.
  * Asynchronous, never synchronises, never allocates.  fp32 accumulation, round-to-nearest-even to bf16;
- * bitwise reproducible.  128x128 blocks with k % 8 == 0, m % 8 == 0, 16-byte aligned X and Y and at least
- * one 128 x 512 tile per compute unit run on the matrix cores; everything else takes a slow generic kernel.
+ * bitwise reproducible.  128x128 blocks (and 64x64 / 32x32 blocks when k is a multiple of the block size and
+ * stacking vertically adjacent block-rows into 128 rows adds at most 2.6x / 4.3x zero fill) with k % 8 == 0,
+ * m % 8 == 0, 16-byte aligned X and Y and at least one 128 x 512 tile per compute unit run on the matrix
+ * cores; everything else takes a slow generic kernel.
  */
 asp_status_t asp_spmm_xt(const asp_handle_t *h, const void *X, void *Y, int64_t N, void *stream);
 
