@@ -248,9 +248,16 @@ def workload(name: str, scale: float = 1.0):
     mm = re.match(r"^(.*)_n(\d+)$", name)
     if mm:
         name, n_override = mm.group(1), int(mm.group(2))
-    if n_override is not None:
+    h_override = None   # "_h<height>": a WCSR workload with another window height (before "_n", "_f32" / "_bf16")
+    mm = re.match(r"^(wcsr_.*)_h(16|32|64)$", name)
+    if mm:
+        name, h_override = mm.group(1), int(mm.group(2))
+    if n_override is not None or h_override is not None:
         w = list(workload(name + ("_" + dt if dt else ""), scale))
-        w[4] = n_override
+        if n_override is not None:
+            w[4] = n_override
+        if h_override is not None:
+            w[2] = h_override
         return tuple(w)
     mm = re.match(r"^bcsr_sweep_b(32|64|128)_s(\d+)$", name)
     if mm:                              # config 5: long prefill, geometric block-row lengths
