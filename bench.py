@@ -149,6 +149,29 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
     if t_reorder is not None:
         res["reorder_s"] = t_reorder
 
+    if with_cpu_baseline and fmt == "bcsr" and dt == "bf16" and not xt and a.m * a.k <= (1 << 28):
+        # context, as in the paper's Section IV-D (kernel speedup over the dense product): the vendor library's dense
+        # bf16 GEMM of the same shape on this machine, A densified with its zeros
+        dense = np.zeros((a.m, a.k), dtype=np.uint16)
+        rows = np.repeat(np.arange(a.m), np.diff(a.row_ptr))
+        dense[rows, a.col_idx] = a.values
+        Ad = torch.from_numpy(dense.view(np.int16)).cuda().view(torch.bfloat16)
+        Bb = Bd.view(torch.bfloat16)
+        for _ in range(3):
+            torch.matmul(Ad, Bb)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            torch.matmul(Ad, Bb)
+        e1.record()
+        torch.cuda.synchronize()
+        dense_ms = e0.elapsed_time(e1) / 10
+        res["dense_gemm_context"] = {"library": "torch.matmul (bf16, vendor GEMM)", "ms": dense_ms,
+                                     "TFLOP/s": 2.0 * a.m * a.k * N / (dense_ms * 1e-3) / 1e12,
+                                     "spmm_speedup_over_dense": dense_ms / kern_ms}
+        del Ad, dense
+
     if with_cpu_baseline:
         import oracle
         # bounded sample: the oracle on a slice of B's columns (column j of C needs column j of B only)

@@ -127,7 +127,8 @@ asp_status_t asp_create_from_csr(const asp_config_t *cfg, int64_t m, int64_t k, 
  * WCSR windows that are split into several tasks: with scratch memory (asp_reserve) the tasks' fp32 partial
  * tiles are added in task order and rounded once; an f32 handle without scratch adds into C with fp32
  * atomics, and only then may those rows differ in the last bits from run to run.  Everything else is
- * bitwise reproducible.
+ * bitwise reproducible.  The device the handle was created on must be the current one (ASP_ERR_INVALID_ARG otherwise)
+ * and stream must belong to it.
  */
 asp_status_t asp_spmm(const asp_handle_t *h, const void *B, void *C, int64_t N, void *stream);
 

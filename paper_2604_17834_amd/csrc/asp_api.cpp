@@ -199,11 +199,22 @@ asp_status_t asp_create_from_csr(const asp_config_t *cfg, int64_t m, int64_t k, 
     return ASP_OK;
 }
 
+// The handle's arrays live on one device; kernels go to the caller's stream, which must belong to it.
+static asp_status_t check_current_device(const asp_handle *h) {
+    int cur = -1;
+    ASP_HIP_TRY(hipGetDevice(&cur));
+    if (cur != h->device)
+        return fail(ASP_ERR_INVALID_ARG, "the handle was created on device " + std::to_string(h->device) +
+                                             ", the current device is " + std::to_string(cur));
+    return ASP_OK;
+}
+
 asp_status_t asp_spmm(const asp_handle_t *h, const void *B, void *C, int64_t N, void *stream) {
     if (!h || !B || !C) return fail(ASP_ERR_INVALID_ARG, "null handle, B or C");
     if (N < 1) return fail(ASP_ERR_INVALID_ARG, "N must be >= 1");
     if (h->device < 0) return fail(ASP_ERR_UNSUPPORTED, "handle was converted on the host only; it has no device arrays");
     if (N > ASP_MAX_N || h->m * N >= (1ll << 40)) return fail(ASP_ERR_UNSUPPORTED, "N too large (ASP_MAX_N, and M x N below 2^40)");
+    if (asp_status_t s = check_current_device(h)) return s;
     if (h->format == ASP_FMT_BCSR) return bcsr_spmm_launch(h, B, C, N, (hipStream_t)stream);
     return wcsr_spmm_launch(h, B, C, N, (hipStream_t)stream);
 }
@@ -238,6 +249,7 @@ asp_status_t asp_spmm_xt(const asp_handle_t *h, const void *X, void *Y, int64_t 
         return fail(ASP_ERR_UNSUPPORTED, "the K-contiguous entry is built for bf16 BCSR handles only");
     if (N > ASP_MAX_N || h->m * N >= (1ll << 40) || h->k * N >= (1ll << 40))
         return fail(ASP_ERR_UNSUPPORTED, "N too large (ASP_MAX_N, and M x N, K x N below 2^40)");
+    if (asp_status_t s = check_current_device(h)) return s;
     return bcsr_spmm_xt_launch(h, X, Y, N, (hipStream_t)stream);
 }
 
