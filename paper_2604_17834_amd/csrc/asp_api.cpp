@@ -30,6 +30,7 @@ static void free_device(asp_handle *h) {
     (void)hipFree(h->d_ws);
     (void)hipFree(h->d_c_rank_info);
     (void)hipFree(h->d_c_slice_rows);
+    (void)hipFree(h->d_c_piece_rows);
     (void)hipFree(h->d_c_values);
     if (cur >= 0 && cur != h->device) (void)hipSetDevice(cur);
 }
@@ -98,6 +99,7 @@ static asp_status_t create_impl(const asp_config_t *cfg, int64_t m, int64_t k, i
         if (h->has_comp) {
             if ((s = upload(&h->d_c_rank_info, h->hc.rank_info.data(), h->hc.rank_info.size() * 4, stream))) return s;
             if ((s = upload(&h->d_c_slice_rows, h->hc.slice_rows.data(), h->hc.slice_rows.size() * 4, stream))) return s;
+            if ((s = upload(&h->d_c_piece_rows, h->hc.piece_rows.data(), h->hc.piece_rows.size() * 4, stream))) return s;
             if ((s = upload(&h->d_c_values, h->hc.packed.data(), h->hc.packed.size(), stream))) return s;
         }
         ASP_HIP_TRY(hipStreamSynchronize(stream));

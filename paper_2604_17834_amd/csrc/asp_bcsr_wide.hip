@@ -78,13 +78,16 @@ struct WideCfg {
 //
 // GATHER = true: the composite form of a matrix with 64x64 or 32x32 blocks (asp_convert.cpp): a "block" is 128 rows
 // x four 32-wide K slices that multiply four separately placed 32-row strips of the dense operand;
-// block_col_idx then holds, per block, the first dense row of each slice (int4) instead of a block column.
+// block_col_idx then holds, per block, the first dense row of each slice (int4) instead of a block column, the
+// block-row number in rank_info is a super-row number, and piece_rows gives, per super-row, the first row of C of
+// each of the tile's four 32-row pieces (-1: the piece has no rows; its accumulators are zeros).
 // Needs KAL (every strip lies inside K).
 template <bool KAL, bool XT, bool GATHER>
 __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     const int4 *__restrict__ rank_info, const int32_t *__restrict__ block_col_idx,
     const uint16_t *__restrict__ a_packed, const uint16_t *__restrict__ B, uint16_t *__restrict__ C, int M, int K,
-    int N, int n_rows, int n_brows, int n_blocks, int n_tiles, int group_n, int xcd_aware, XcdRuns runs) {
+    int N, int n_rows, int n_brows, int n_blocks, int n_tiles, int group_n, int xcd_aware, XcdRuns runs,
+    const int4 *__restrict__ piece_rows) {
     using Cfg = WideCfg;
     constexpr int NS = Cfg::NS, NW = Cfg::NW, KS = Cfg::KS, BR = Cfg::BR, BN = Cfg::BN, MT = Cfg::MT, NTL = Cfg::NTL;
     __shared__ __attribute__((aligned(1024))) uint8_t lds[Cfg::LDS_BYTES];
@@ -109,9 +112,16 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     // (XT: the block-row's outputs are up to 256 bytes in every row of Y)
     auto clear_empty_rows = [&]() __attribute__((always_inline)) {
         const uint4 z = {0u, 0u, 0u, 0u};
-        for (int e = n_rows; e < n_brows; ++e) {
-            const int br = __builtin_amdgcn_readfirstlane(rank_info[e].x);
-            const int r0 = br * Cfg::BR, r1 = r0 + Cfg::BR < M ? r0 + Cfg::BR : M;
+        for (int e = n_rows * (GATHER ? 4 : 1); e < n_brows * (GATHER ? 4 : 1); ++e) {
+            // GATHER: piece e % 4 of super-row e / 4, 32 rows starting at its entry of piece_rows
+            const int br = __builtin_amdgcn_readfirstlane(rank_info[GATHER ? e >> 2 : e].x);
+            int r0 = br * Cfg::BR, r1 = r0 + Cfg::BR < M ? r0 + Cfg::BR : M;
+            if (GATHER) {
+                const int4 pr = piece_rows[br];
+                r0 = __builtin_amdgcn_readfirstlane((e & 3) == 0 ? pr.x : (e & 3) == 1 ? pr.y : (e & 3) == 2 ? pr.z : pr.w);
+                if (r0 < 0 || r0 >= M) continue;
+                r1 = r0 + 32 < M ? r0 + 32 : M;
+            }
             if (!XT) {
                 uint16_t *dst = C + (int64_t)r0 * N;
                 const int64_t n16 = (int64_t)(r1 - r0) * N / 8;
@@ -506,13 +516,26 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
 
         // the buffer of the slice just finished (always the last one of the ring) is the spare one
         // until the next barrier
-        const bool interior = c_br * BR + BR <= M && c_n0 + BN <= N;
+        // GATHER: where the tile's four 32-row pieces go (issued here, with the loads of decode)
+        const int4 prow = GATHER ? piece_rows[c_br] : int4{0, 0, 0, 0};
+        const int pmin = prow.x < prow.y ? (prow.x < prow.z ? (prow.x < prow.w ? prow.x : prow.w) : (prow.z < prow.w ? prow.z : prow.w))
+                                         : (prow.y < prow.z ? (prow.y < prow.w ? prow.y : prow.w) : (prow.z < prow.w ? prow.z : prow.w));
+        const int pmax = prow.x > prow.y ? (prow.x > prow.z ? (prow.x > prow.w ? prow.x : prow.w) : (prow.z > prow.w ? prow.z : prow.w))
+                                         : (prow.y > prow.z ? (prow.y > prow.w ? prow.y : prow.w) : (prow.z > prow.w ? prow.z : prow.w));
+        const bool rows_interior = GATHER ? __builtin_amdgcn_readfirstlane(pmin >= 0 && pmax + 32 <= M) : c_br * BR + BR <= M;
+        const bool interior = rows_interior && c_n0 + BN <= N;
         uint8_t *sc = lds + (NS - 1) * Cfg::STAGE + wave * Cfg::C_WAVE;
         // a piece = 32 rows x 128 columns of the output matrix: rows of C and the wave's 128 columns, or
         // (XT) 32 of the wave's tokens = rows of Y and the block-row's 128 outputs
         const int out_ld = XT ? M : N, out_rows = XT ? N : M, out_cols = XT ? M : N;
-        const int grow0 = (XT ? c_n0 + wave * Cfg::TN : c_br * BR) + lane / Cfg::CPR;
-        const int gcol0 = (XT ? c_br * BR : c_n0 + wave * Cfg::TN) + (lane % Cfg::CPR) * 8;
+        // GATHER: the tile's 128 rows of the product (rows of C, or XT: columns of Y) are four separately placed
+        // pieces of 32; a 16-byte unit never straddles two of them
+        const int xt_piece = (lane % Cfg::CPR) >> 2;  // XT: the piece this lane's 8 outputs belong to
+        const int xt_pbase = xt_piece == 0 ? prow.x : xt_piece == 1 ? prow.y : xt_piece == 2 ? prow.z : prow.w;
+        const int grow0 = (XT ? c_n0 + wave * Cfg::TN : GATHER ? 0 : c_br * BR) + lane / Cfg::CPR;
+        const int gcol0 = XT ? (GATHER ? xt_pbase + ((lane % Cfg::CPR) & 3) * 8 : c_br * BR + (lane % Cfg::CPR) * 8)
+                             : c_n0 + wave * Cfg::TN + (lane % Cfg::CPR) * 8;
+        const bool xt_piece_ok = !(XT && GATHER) || xt_pbase >= 0;
         const uint8_t *scl = sc + (lane / Cfg::CPR) * Cfg::C_PITCH + (lane % Cfg::CPR) * 16;
 #pragma unroll
         for (int o = 0; o < 4; ++o) {
@@ -531,7 +554,11 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
                 }
             }
             // LDS is in order within a wave: the reads below see the writes above
-            uint16_t *cdst = C + (int64_t)(grow0 + o * 32) * out_ld + gcol0;
+            // first row of this piece: XT pieces are 32 tokens; otherwise rows of C
+            const int prow_o = o == 0 ? prow.x : o == 1 ? prow.y : o == 2 ? prow.z : prow.w;
+            const int rbase = (!XT && GATHER) ? prow_o : o * 32;
+            const bool piece_ok = (!XT && GATHER) ? prow_o >= 0 : xt_piece_ok;
+            uint16_t *cdst = C + (int64_t)(grow0 + rbase) * out_ld + gcol0;
             if (interior) {
 #pragma unroll
                 for (int it = 0; it < 32 / Cfg::RPI; ++it) {
@@ -542,7 +569,7 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
 #pragma unroll
                 for (int it = 0; it < 32 / Cfg::RPI; ++it) {
                     uint4 v = *(const uint4 *)(scl + it * Cfg::RPI * Cfg::C_PITCH);
-                    if (grow0 + o * 32 + it * Cfg::RPI < out_rows && gcol0 < out_cols)
+                    if (piece_ok && grow0 + rbase + it * Cfg::RPI < out_rows && gcol0 < out_cols)
                         store_c16(cdst + (int64_t)it * Cfg::RPI * out_ld, v);
                 }
             }
@@ -615,15 +642,16 @@ struct WideOperand {
     const std::vector<int64_t> *weight_prefix;
     int64_t n_rows, n_brows, n_blocks;  // non-empty block-rows, all block-rows, blocks
     bool composite;
+    const int4 *piece_rows;  // composite: first row of C of each 32-row piece of a super-row
 };
 static WideOperand wide_operand(const asp_handle *h) {
     if (h->b_row == 128)
         return WideOperand{(const int4 *)h->d_rank_info, h->d_col_idx,          (const uint16_t *)h->d_values,
                            &h->hb.sorted_weight_prefix,  h->hb.n_nonempty,      h->n_brows,
-                           h->n_units,                   false};
+                           h->n_units,                   false,                 nullptr};
     return WideOperand{(const int4 *)h->d_c_rank_info, h->d_c_slice_rows,     (const uint16_t *)h->d_c_values,
                        &h->hc.sorted_weight_prefix,    h->hc.n_nonempty,      h->c_n_brows,
-                       h->c_n_units,                   true};
+                       h->c_n_units,                   true,                  (const int4 *)h->d_c_piece_rows};
 }
 
 template <bool XT>
@@ -652,7 +680,7 @@ static void launch_wide(const asp_handle *h, const void *B, void *C, int64_t N, 
 #define ASP_LAUNCH_WIDE(KAL, GATHER)                                                                                   \
     hipLaunchKernelGGL((bcsr_spmm_wide_kernel<KAL, XT, GATHER>), grid, block, 0, stream, op.rank_info, op.cols, op.values, \
                        (const uint16_t *)B, (uint16_t *)C, (int)h->m, (int)h->k, (int)N, (int)n_rows, (int)op.n_brows,  \
-                       (int)op.n_blocks, n_tiles, group_n, env_xcd, runs)
+                       (int)op.n_blocks, n_tiles, group_n, env_xcd, runs, op.piece_rows)
     if (op.composite) ASP_LAUNCH_WIDE(true, true);  // built only for K % block size == 0
     else if (h->k % 128 == 0) ASP_LAUNCH_WIDE(true, false);
     else ASP_LAUNCH_WIDE(false, false);

@@ -198,25 +198,112 @@ void bcsr_build_schedule(HostBcsr &b) {
 }
 
 // Composite form of a bf16 BCSR matrix with 64x64 or 32x32 blocks, for the kernel written for 128x128 blocks
-// (Section II-C's block product, regrouped): R = 128 / b vertically adjacent block-rows make one 128-row
-// super-row; the union of their block columns is cut into groups of R; a composite block holds, for each of its
-// R columns j, the b-wide column strip [block(r0, j); ...; block(r0 + R - 1, j)] (zeros where a block is not
-// stored) as b / 32 consecutive 32-wide K slices.  slice_rows gives, per composite block, the first row of B that
-// each of its four K slices multiplies (for a plain 128x128 block these would be 128 J + 0, 32, 64, 96).
-// Strips that pad the last group are zeros and repeat the rows of the last real strip.
+// (Section II-C's block product, regrouped): R = 128 / b block-rows make one 128-row super-row; the union of their
+// block columns is cut into groups of R; a composite block holds, for each of its R columns j, the b-wide column
+// strip [block(r_0, j); ...; block(r_{R-1}, j)] of the super-row's members (zeros where a block is not stored) as
+// b / 32 consecutive 32-wide K slices.  slice_rows gives, per composite block, the first row of B that each of
+// its four K slices multiplies (for a plain 128x128 block these would be 128 J + 0, 32, 64, 96).  Strips that pad
+// the last group are zeros and repeat the rows of the last real strip.
+//
+// Members of a super-row need not be adjacent: every absent block of a strip is computed as zeros, so block-rows
+// with similar block columns are put together (greedy: longest unassigned block-row first, then R - 1 times the
+// unassigned block-row with the largest Jaccard index against the group's union of columns; on 50-90 %-sparse
+// random masks this stores 12-24 % fewer composite blocks than grouping neighbours).  piece_rows
+// gives, per super-row, the first row of C of each of its four 32-row pieces, -1 for a member that does not
+// exist.  Block-rows without blocks form super-rows of their own at the end (their rows of C are cleared).
 // Returns the work inflation: composite blocks x 128 x 128 over stored blocks x b x b.
 double bcsr_build_composite(const HostBcsr &in, int64_t m, int32_t b, HostBcsr &out) {
     const int64_t nbr = (int64_t)in.block_row_ptr.size() - 1;
-    const int32_t R = 128 / b, spv = b / 32;  // strips per composite block; K slices per strip
-    const int64_t nsr = ceil_div(m, 128);
+    const int32_t R = 128 / b, spv = b / 32;  // members of a super-row = strips per composite block; K slices per strip
+    (void)m;
+    auto len = [&](int64_t r) { return in.block_row_ptr[r + 1] - in.block_row_ptr[r]; };
+    auto cols = [&](int64_t r) { return in.block_col_idx.data() + in.block_row_ptr[r]; };
+
+    // ---- grouping ----------------------------------------------------------------------------------------
+    int32_t nbc = 0;
+    for (int32_t c : in.block_col_idx) nbc = std::max(nbc, c + 1);
+    std::vector<int32_t> inv_ptr((size_t)nbc + 1, 0), inv(in.block_col_idx.size());
+    for (int32_t c : in.block_col_idx) ++inv_ptr[c + 1];
+    for (int32_t c = 0; c < nbc; ++c) inv_ptr[c + 1] += inv_ptr[c];
+    {
+        std::vector<int32_t> fill(inv_ptr.begin(), inv_ptr.end() - 1);
+        for (int64_t r = 0; r < nbr; ++r)
+            for (int32_t t = 0; t < len(r); ++t) inv[fill[cols(r)[t]]++] = (int32_t)r;
+    }
+    std::vector<int32_t> order;
+    for (int64_t r = 0; r < nbr; ++r)
+        if (len(r) > 0) order.push_back((int32_t)r);
+    std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return len(x) > len(y); });
+    std::vector<uint8_t> taken((size_t)nbr, 0), in_union((size_t)nbc, 0);
+    std::vector<int32_t> shared((size_t)nbr, 0), touched, uni;
+    std::vector<int32_t> members;  // R per super-row, -1 = none
+    const int64_t budget = 1 << 18;  // shared-column counts examined per choice: bounds the work on dense matrices
+    for (int32_t seed : order) {
+        if (taken[seed]) continue;
+        taken[seed] = 1;
+        const size_t g0 = members.size();
+        members.push_back(seed);
+        uni.assign(cols(seed), cols(seed) + len(seed));
+        for (int32_t c : uni) in_union[c] = 1;
+        while (members.size() - g0 < (size_t)R) {
+            touched.clear();
+            int64_t spent = 0;
+            for (int32_t c : uni) {
+                for (int32_t q = inv_ptr[c]; q < inv_ptr[c + 1] && spent < budget; ++q, ++spent) {
+                    const int32_t r = inv[q];
+                    if (taken[r]) continue;
+                    if (shared[r]++ == 0) touched.push_back(r);
+                }
+                if (spent >= budget) break;
+            }
+            // best Jaccard index with the group's union: shared / (union + own - shared), compared as fractions
+            int32_t best = -1;
+            int64_t best_num = 0, best_den = 1;
+            const int64_t usize = (int64_t)uni.size();
+            for (int32_t r : touched) {
+                const int64_t num = shared[r], den = usize + len(r) - shared[r];
+                const int64_t lhs = num * best_den, rhs = best_num * den;
+                if (best < 0 || lhs > rhs || (lhs == rhs && r < best)) best = r, best_num = num, best_den = den;
+                shared[r] = 0;
+            }
+            if (best < 0) break;  // nobody shares a column: the group stays short
+            taken[best] = 1;
+            members.push_back(best);
+            for (int32_t t = 0; t < len(best); ++t) {
+                const int32_t c = cols(best)[t];
+                if (!in_union[c]) in_union[c] = 1, uni.push_back(c);
+            }
+        }
+        for (int32_t c : uni) in_union[c] = 0;
+        // members in ascending block-row order (rows of C of a tile ascend), padded with -1
+        std::sort(members.begin() + g0, members.end());
+        while (members.size() - g0 < (size_t)R) members.push_back(-1);
+    }
+    {   // block-rows without blocks
+        size_t g0 = members.size();
+        for (int64_t r = 0; r < nbr; ++r)
+            if (len(r) == 0) {
+                members.push_back((int32_t)r);
+                if (members.size() - g0 == (size_t)R) g0 = members.size();
+            }
+        while ((members.size() - g0) % R != 0) members.push_back(-1);
+    }
+    const int64_t nsr = (int64_t)members.size() / R;
+
+    // ---- composite blocks --------------------------------------------------------------------------------
     out = HostBcsr();
     out.block_row_ptr.assign(nsr + 1, 0);
-    std::vector<std::vector<int32_t>> uni((size_t)nsr);
+    out.piece_rows.assign((size_t)nsr * 4, -1);
+    std::vector<std::vector<int32_t>> unis((size_t)nsr);
     parallel_chunks(nsr, 16, [&](unsigned, int64_t lo, int64_t hi) {
         for (int64_t sr = lo; sr < hi; ++sr) {
-            auto &u = uni[sr];
-            const int64_t r0 = sr * R, r1 = std::min<int64_t>(nbr, r0 + R);
-            u.assign(in.block_col_idx.begin() + in.block_row_ptr[r0], in.block_col_idx.begin() + in.block_row_ptr[r1]);
+            auto &u = unis[sr];
+            for (int32_t t = 0; t < R; ++t) {
+                const int32_t br = members[sr * R + t];
+                if (br < 0) continue;
+                u.insert(u.end(), cols(br), cols(br) + len(br));
+                for (int32_t i = 0; i < spv; ++i) out.piece_rows[4 * sr + t * spv + i] = br * b + 32 * i;
+            }
             std::sort(u.begin(), u.end());
             u.erase(std::unique(u.begin(), u.end()), u.end());
             out.block_row_ptr[sr + 1] = (int32_t)ceil_div((int64_t)u.size(), R);
@@ -231,8 +318,7 @@ double bcsr_build_composite(const HostBcsr &in, int64_t m, int32_t b, HostBcsr &
     uint16_t *dst = (uint16_t *)out.blocks.data();
     parallel_chunks(nsr, 4, [&](unsigned, int64_t lo, int64_t hi) {
         for (int64_t sr = lo; sr < hi; ++sr) {
-            const auto &u = uni[sr];
-            const int64_t r0 = sr * R, r1 = std::min<int64_t>(nbr, r0 + R);
+            const auto &u = unis[sr];
             for (int64_t c = out.block_row_ptr[sr]; c < out.block_row_ptr[sr + 1]; ++c) {
                 const int64_t first = (c - out.block_row_ptr[sr]) * R;
                 for (int32_t v = 0; v < R; ++v) {
@@ -240,14 +326,15 @@ double bcsr_build_composite(const HostBcsr &in, int64_t m, int32_t b, HostBcsr &
                     const int32_t j = u[real ? first + v : u.size() - 1];
                     for (int32_t t = 0; t < spv; ++t) out.slice_rows[4 * c + v * spv + t] = j * b + 32 * t;
                     if (!real) continue;
-                    for (int64_t br = r0; br < r1; ++br) {
-                        const int32_t *cb = in.block_col_idx.data() + in.block_row_ptr[br];
-                        const int32_t *ce = in.block_col_idx.data() + in.block_row_ptr[br + 1];
+                    for (int32_t t = 0; t < R; ++t) {
+                        const int32_t br = members[sr * R + t];
+                        if (br < 0) continue;
+                        const int32_t *cb = cols(br), *ce = cb + len(br);
                         const int32_t *hit = std::lower_bound(cb, ce, j);
                         if (hit == ce || *hit != j) continue;
                         const uint16_t *sb = src + (int64_t)(hit - in.block_col_idx.data()) * b * b;
                         for (int32_t r = 0; r < b; ++r)
-                            std::memcpy(dst + c * 128 * 128 + ((br - r0) * b + r) * 128 + v * b, sb + (int64_t)r * b,
+                            std::memcpy(dst + c * 128 * 128 + ((int64_t)t * b + r) * 128 + v * b, sb + (int64_t)r * b,
                                         (size_t)b * 2);
                     }
                 }

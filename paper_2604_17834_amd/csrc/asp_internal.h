@@ -74,6 +74,7 @@ struct HostBcsr {
     std::vector<int64_t> sorted_weight_prefix; // [n_brows + 1]
     int64_t n_nonempty = 0;                    // block-rows with at least one stored block (they come first)
     std::vector<int32_t> slice_rows;           // composite form only: [blocks][4] first row of B of each K slice
+    std::vector<int32_t> piece_rows;           // composite form only: [super-rows][4] first row of C of each 32-row piece, -1 = none
 };
 
 struct HostWcsr {
@@ -121,6 +122,7 @@ struct asp_handle {
     int64_t c_n_brows = 0, c_n_units = 0;  // super-rows, composite blocks
     int32_t *d_c_rank_info = nullptr;
     int32_t *d_c_slice_rows = nullptr;     // [composite blocks][4]
+    int32_t *d_c_piece_rows = nullptr;     // [super-rows][4]
     void *d_c_values = nullptr;
     asp::HostWcsr hw;  // WCSR: kept only in host-convert mode (device arrays are canonical)
 

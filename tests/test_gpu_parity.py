@@ -251,8 +251,8 @@ def _plan_bn_b(a, b, N):
 
 @pytest.mark.parametrize("b", [64, 32])
 @pytest.mark.parametrize("m,k,N,sparsity,geometric", [
-    (2048, 1024, 8192, 0.5, True),          # aligned everywhere
-    (2048 - 40, 1024, 8192 + 72, 0.5, True),  # last block-row and last super-row ragged, N tail
+    (2560, 1024, 8192, 0.5, True),          # aligned everywhere
+    (2560 - 40, 1024, 8192 + 72, 0.5, True),  # last block-row ragged (its second piece lies past M), N tail
     (4096, 2048, 4096, 0.3, False),         # dense-ish Bernoulli mask: nearly every strip is full
     (4096, 512, 4096 - 8, 0.6, False),
 ])
@@ -295,7 +295,7 @@ def test_bcsr_small_blocks_composite_empty_rows_rerun_and_identity(b):
 def test_bcsr_small_blocks_composite_equals_small_block_kernel_within_rounding(b):
     # the same handle on a width where the composite form is not used (too few tiles) gives the same columns up
     # to the order of the fp32 sums: both must sit inside the oracle's bound, and mostly agree bit for bit
-    a = synth.block_sparse_geometric(2048, 2048, b, b, 0.5, seed=65 + b, dtype="bf16")
+    a = synth.block_sparse_geometric(2560, 2048, b, b, 0.5, seed=65 + b, dtype="bf16")
     B = synth.dense_normal(a.k, 8192, "bf16", seed=66)
     h = asp.asp_create_from_csr("bcsr", "bf16", b, b, a.m, a.k, a.row_ptr, a.col_idx, a.values)
     try:
@@ -311,8 +311,16 @@ def test_bcsr_small_blocks_composite_equals_small_block_kernel_within_rounding(b
 
 @pytest.mark.parametrize("b", [64, 32])
 def test_bcsr_xt_small_blocks_composite_parity(b):
-    m, k, N = 2048, 1024 + b, 8192 + 40
+    m, k, N = 3072, 1024 + b, 8192 + 40
     a = synth.block_sparse_geometric(m, k, b, b, 0.5, seed=67 + b, dtype="bf16")
+    # every fifth block-row empty: their outputs are cleared, in 64-byte pieces of the rows of Y
+    keep = np.ones(a.nnz, dtype=bool)
+    rows = np.repeat(np.arange(a.m), np.diff(a.row_ptr))
+    keep[(rows // b) % 5 == 1] = False
+    rp = np.zeros(a.m + 1, dtype=np.int64)
+    np.add.at(rp, rows[keep] + 1, 1)
+    a = synth.Csr(a.m, a.k, np.cumsum(rp).astype(np.int32), a.col_idx[keep], a.values[keep], a.dtype)
+    assert _plan_bn_b(a, b, N) == 512
     X = synth.dense_normal(N, k, "bf16", seed=68)
     Y = gpu_spmm_xt(a, b, X)
     tok = np.r_[0:48, 4000:4048, N - 48:N]
