@@ -792,6 +792,38 @@ def test_random_configurations_parity(seed):
     check_against_oracle(a, B, C)
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_small_block_configurations_on_wide_tiles(seed):
+    # seeded draw over the shapes that put 64x64 / 32x32 blocks on the 128x512-tile kernel (composite form):
+    # block masks from dense to very sparse, empty block-rows, ragged M, any K that is a multiple of the block
+    # size, N with and without a tail tile; both entries
+    rng = np.random.default_rng(7100 + seed)
+    b = int(rng.choice([32, 64]))
+    m = int(rng.integers(2300, 6000))
+    k = b * int(rng.integers(1, 40))
+    N = 8 * int(rng.integers(4096 // 8, 9000 // 8))
+    sparsity = float(rng.choice([0.0, 0.3, 0.6, 0.8, 0.9, 0.97]))
+    gen = synth.block_sparse_geometric if rng.random() < 0.5 else synth.block_sparse_bernoulli
+    a = gen(m, k, b, b, sparsity, seed=7200 + seed, dtype="bf16")
+    if rng.random() < 0.5:   # empty block-rows, singly and in runs
+        keep = np.ones(a.nnz, dtype=bool)
+        rows = np.repeat(np.arange(a.m), np.diff(a.row_ptr))
+        brow = rows // b
+        keep[(brow % 6 == 2) | ((brow >= 9) & (brow < 15))] = False
+        rp = np.zeros(a.m + 1, dtype=np.int64)
+        np.add.at(rp, rows[keep] + 1, 1)
+        a = synth.Csr(a.m, a.k, np.cumsum(rp).astype(np.int32), a.col_idx[keep], a.values[keep], a.dtype)
+    cols = np.sort(rng.choice(N, 96, replace=False))
+    if rng.random() < 0.5 or m % 8 != 0:
+        B = synth.dense_normal(k, N, "bf16", seed=7300 + seed)
+        C = gpu_spmm(a, "bcsr", b, b, B)
+        check_against_oracle(a, B, C, cols)
+    else:
+        X = synth.dense_normal(N, k, "bf16", seed=7300 + seed)
+        Y = gpu_spmm_xt(a, b, X)
+        check_against_oracle(a, np.ascontiguousarray(X[cols].T), np.ascontiguousarray(Y[cols].T))
+
+
 def test_create_reserve_destroy_returns_device_memory():
     a = synth.zipf_graph(20000, 20000, 12 * 20000, seed=90, cap=3000, dtype="bf16")
     b = synth.block_sparse_bernoulli(1024, 1024, 64, 64, 0.7, seed=91)
