@@ -9,7 +9,7 @@ protocol of the paper's Section IV (10 warm-up + 100 timed launches, throughput 
 the original matrix).  The conversion time is reported separately in the same JSON line.
 
 Prints ONE JSON line.  `value` uses the wall-clock time of the K timed steps; `roofline.achieved` uses the
-average kernel time measured with events on the launch stream.
+average duration of a launch from one pair of events on the launch stream around the same K steps.
 """
 import argparse
 import json
@@ -45,6 +45,7 @@ def _measured_traffic(workload):
 
 
 _DENSE_MEMO = {}
+SINGLE_LAUNCHES = False   # --single-launches
 
 
 def _dense_normal(synth, rows, cols, dt, seed):
@@ -97,18 +98,29 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
     for _ in range(warmup):
         spmm(h, bp, cp, N, stream)
     torch.cuda.synchronize()
-    starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
-    ends = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    # the timed region: exactly `steps` calls back to back, bracketed by a synchronisation on both sides (wall
+    # clock -> value) and by one pair of events on the launch stream (-> average duration of a launch)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     w0 = time.perf_counter()
+    ev0.record()
     for i in range(steps):
-        starts[i].record()
         spmm(h, bp, cp, N, stream)
-        ends[i].record()
+    ev1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - w0) * 1e3 / steps
-    per = np.array([s.elapsed_time(e) for s, e in zip(starts, ends)])
-    kern_ms = float(per.mean())
+    kern_ms = ev0.elapsed_time(ev1) / steps
+    per = None
+    if SINGLE_LAUNCHES:
+        # a second, untimed pass with events around every call: single launches, each on an otherwise idle GPU
+        starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+        ends = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+        for i in range(steps):
+            starts[i].record()
+            spmm(h, bp, cp, N, stream)
+            ends[i].record()
+        torch.cuda.synchronize()
+        per = np.array([s.elapsed_time(e) for s, e in zip(starts, ends)])
 
     flops_eff = 2.0 * a.nnz * N
     esz = 2 if dt == "bf16" else 4
@@ -138,7 +150,9 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = _measured_traffic(name)
     roof["kernel_ms_avg"] = kern_ms
-    roof["kernel_ms_median"] = float(np.median(per))
+    if per is not None:   # --single-launches
+        roof["single_launch_ms_median"] = float(np.median(per))
+        roof["single_launch_ms_avg"] = float(per.mean())
 
     res = {
         "workload": name, "format": fmt, "dtype": dt, "b_row": b_row, "b_col": b_col, "m": a.m, "k": a.k, "N": N, "nnz": a.nnz,
@@ -346,12 +360,16 @@ def main():
                          "which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
     ap.add_argument("--mlp-chain", action="store_true",
                     help="time gate, up and down projections of the feed-forward block chained through asp_spmm_xt")
+    ap.add_argument("--single-launches", action="store_true",
+                    help="after the timed region, time the same number of calls one by one (events around each)")
     ap.add_argument("--sweep", action="store_true",
                     help="the long-prefill BCSR grid (block sizes x sparsities) and the band + long rows WCSR workload at "
                          "both widths: one JSON object, no CPU baseline")
     ap.add_argument("--ablation", action="store_true",
                     help="run the BCSR workload once per kernel variant (child processes) and print one JSON object")
     args = ap.parse_args()
+    global SINGLE_LAUNCHES
+    SINGLE_LAUNCHES = args.single_launches
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (one MI355X, no collectives); run with --gpus 1",
               file=sys.stderr)
