@@ -46,6 +46,7 @@ def _measured_traffic(workload):
 
 _DENSE_MEMO = {}
 SINGLE_LAUNCHES = False   # --single-launches
+WARMUP_MIN_MS = 60.0      # --warmup-min-ms
 
 
 def _dense_normal(synth, rows, cols, dt, seed):
@@ -95,8 +96,16 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
         Cd = torch.empty((N, a.m) if xt else (a.m, N), dtype=torch.float32, device="cuda")
     bp, cp = Bd.data_ptr(), Cd.data_ptr()
 
-    for _ in range(warmup):
+    # untimed warm-up: `warmup` calls, and at least WARMUP_MIN_MS of them -- the GPU takes about 30 ms under load to
+    # reach the clocks it then holds (measured: the first ~100 launches of the 0.27 ms BCSR workload run 8 % slower
+    # than all later ones, whatever the split between warm-up and timed calls)
+    warm_run = 0
+    t_w = time.perf_counter()
+    while warm_run < warmup or (time.perf_counter() - t_w) * 1e3 < WARMUP_MIN_MS:
         spmm(h, bp, cp, N, stream)
+        warm_run += 1
+        if warm_run % 16 == 0:
+            torch.cuda.synchronize()   # keeps the loop's clock honest: launches are asynchronous
     torch.cuda.synchronize()
     # the timed region: exactly `steps` calls back to back, bracketed by a synchronisation on both sides (wall
     # clock -> value) and by one pair of events on the launch stream (-> average duration of a launch)
@@ -158,7 +167,7 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
         "workload": name, "format": fmt, "dtype": dt, "b_row": b_row, "b_col": b_col, "m": a.m, "k": a.k, "N": N, "nnz": a.nnz,
         "fill_ratio": info.fill_ratio, "bn": plan.bn, "workgroups": int(plan.workgroups),
         "value": flops_eff / (wall_ms * 1e-3) / 1e9, "ms_per_step": wall_ms, "roofline": roof,
-        "convert_s": t_convert, "generate_s": t_gen, **extra,
+        "convert_s": t_convert, "generate_s": t_gen, "warmup_calls_run": warm_run, **extra,
     }
     if t_reorder is not None:
         res["reorder_s"] = t_reorder
@@ -360,6 +369,8 @@ def main():
                          "which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
     ap.add_argument("--mlp-chain", action="store_true",
                     help="time gate, up and down projections of the feed-forward block chained through asp_spmm_xt")
+    ap.add_argument("--warmup-min-ms", type=float, default=60.0,
+                    help="the untimed warm-up runs at least --warmup calls and at least this long (0: calls only)")
     ap.add_argument("--single-launches", action="store_true",
                     help="after the timed region, time the same number of calls one by one (events around each)")
     ap.add_argument("--sweep", action="store_true",
@@ -368,8 +379,9 @@ def main():
     ap.add_argument("--ablation", action="store_true",
                     help="run the BCSR workload once per kernel variant (child processes) and print one JSON object")
     args = ap.parse_args()
-    global SINGLE_LAUNCHES
+    global SINGLE_LAUNCHES, WARMUP_MIN_MS
     SINGLE_LAUNCHES = args.single_launches
+    WARMUP_MIN_MS = args.warmup_min_ms
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (one MI355X, no collectives); run with --gpus 1",
               file=sys.stderr)
@@ -420,6 +432,7 @@ def main():
         "metric": "effective SpMM GFLOP/s (2*nnz*N/t), BCSR gate_proj 18944x3584 bf16 128x128 blocks 90% sparse, N=16384"
                   if args.workload == "bcsr_gate_proj" else "effective SpMM GFLOP/s (2*nnz*N/t)",
         "value": main_res["value"], "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "warmup_min_ms": args.warmup_min_ms, "warmup_calls_run": main_res["warmup_calls_run"],
         "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": main_res["dtype"], "data": "synthetic",
         "config": {"workload": args.workload, **{k: main_res[k] for k in

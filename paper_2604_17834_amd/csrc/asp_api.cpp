@@ -65,8 +65,8 @@ static asp_status_t create_impl(const asp_config_t *cfg, int64_t m, int64_t k, i
         // Smaller blocks: the kernel for 128-row tiles on the composite form (asp_convert.cpp) beats the small-block
         // kernel, which reads twice / four times the LDS bytes per MFMA, until the zero fill outweighs that.
         // Measured on 8192 x 8192 matrices with geometric block-row lengths (N = 65536) at 50 / 75 / 90 / 95 / 99 %
-        // block sparsity: 64x64 blocks, fill 1.22 / 1.44 / 1.70 / 1.78 / 2.04 -> 1.92 / 1.77 / 1.41 / 1.32 / 1.10
-        // times faster; 32x32 blocks, fill 1.60 / 2.09 / 2.73 / 3.21 / 3.77 -> 2.56 / 2.30 / 1.65 / 1.21 / 1.04.
+        // block sparsity: 64x64 blocks, fill 1.22 / 1.44 / 1.70 / 1.78 / 2.04 -> 1.98 / 1.84 / 1.41 / 1.38 / 1.13
+        // times faster; 32x32 blocks, fill 1.60 / 2.09 / 2.73 / 3.21 / 3.77 -> 2.72 / 2.44 / 1.68 / 1.22 / 1.08.
         // With super-rows of neighbouring block-rows (more fill) the break-even was at fill 2.6 / 4.3.
         // ASP_BCSR_COMPOSITE=0/1 is a benchmarking switch.
         if (cfg->dtype == ASP_DT_BF16 && cfg->b_row < 128 && k % cfg->b_row == 0 && h->n_units > 0) {
