@@ -152,8 +152,8 @@ asp_status_t asp_reserve(asp_handle_t *h, int64_t N);
  * X: DEVICE, N x k row-major (leading dimension k).  Y: DEVICE, N x m row-major (leading dimension m), fully
  * overwritten; Y must not alias X.  1 <= N <= ASP_MAX_N.  BCSR handles (bf16) only; others return ASP_ERR_UNSUPPORTED.
  * Asynchronous, never synchronises, never allocates.  fp32 accumulation, round-to-nearest-even to bf16;
- * bitwise reproducible.  128x128 blocks (and 64x64 / 32x32 blocks when k is a multiple of the block size and
- * stacking vertically adjacent block-rows into 128 rows adds at most 2.6x / 4.3x zero fill) with k % 8 == 0,
+ * bitwise reproducible.  128x128 blocks (and 64x64 / 32x32 blocks when k >= 32 and grouping their block-rows
+ * into 128-row tiles adds at most 2.6x / 4.3x zero fill) with k % 8 == 0,
  * m % 8 == 0, 16-byte aligned X and Y and at least one 128 x 512 tile per compute unit run on the matrix
  * cores; everything else takes a slow generic kernel.
  */

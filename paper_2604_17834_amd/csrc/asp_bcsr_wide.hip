@@ -81,7 +81,8 @@ struct WideCfg {
 // block_col_idx then holds, per block, the first dense row of each slice (int4) instead of a block column, the
 // block-row number in rank_info is a super-row number, and piece_rows gives, per super-row, the first row of C of
 // each of the tile's four 32-row pieces (-1: the piece has no rows; its accumulators are zeros).
-// Needs KAL (every strip lies inside K).
+// Runs as KAL: the composite form keeps every slice inside K (the slices of a partly filled last block column start
+// early enough to end at K).
 template <bool KAL, bool XT, bool GATHER>
 __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     const int4 *__restrict__ rank_info, const int32_t *__restrict__ block_col_idx,
@@ -681,7 +682,7 @@ static void launch_wide(const asp_handle *h, const void *B, void *C, int64_t N, 
     hipLaunchKernelGGL((bcsr_spmm_wide_kernel<KAL, XT, GATHER>), grid, block, 0, stream, op.rank_info, op.cols, op.values, \
                        (const uint16_t *)B, (uint16_t *)C, (int)h->m, (int)h->k, (int)N, (int)n_rows, (int)op.n_brows,  \
                        (int)op.n_blocks, n_tiles, group_n, env_xcd, runs, op.piece_rows)
-    if (op.composite) ASP_LAUNCH_WIDE(true, true);  // built only for K % block size == 0
+    if (op.composite) ASP_LAUNCH_WIDE(true, true);  // its slices never reach past K
     else if (h->k % 128 == 0) ASP_LAUNCH_WIDE(true, false);
     else ASP_LAUNCH_WIDE(false, false);
 #undef ASP_LAUNCH_WIDE

@@ -212,7 +212,7 @@ void bcsr_build_schedule(HostBcsr &b) {
 // gives, per super-row, the first row of C of each of its four 32-row pieces, -1 for a member that does not
 // exist.  Block-rows without blocks form super-rows of their own at the end (their rows of C are cleared).
 // Returns the work inflation: composite blocks x 128 x 128 over stored blocks x b x b.
-double bcsr_build_composite(const HostBcsr &in, int64_t m, int32_t b, HostBcsr &out) {
+double bcsr_build_composite(const HostBcsr &in, int64_t m, int64_t k, int32_t b, HostBcsr &out) {
     const int64_t nbr = (int64_t)in.block_row_ptr.size() - 1;
     const int32_t R = 128 / b, spv = b / 32;  // members of a super-row = strips per composite block; K slices per strip
     (void)m;
@@ -324,7 +324,16 @@ double bcsr_build_composite(const HostBcsr &in, int64_t m, int32_t b, HostBcsr &
                 for (int32_t v = 0; v < R; ++v) {
                     const bool real = first + v < (int64_t)u.size();
                     const int32_t j = u[real ? first + v : u.size() - 1];
-                    for (int32_t t = 0; t < spv; ++t) out.slice_rows[4 * c + v * spv + t] = j * b + 32 * t;
+                    // a slice must not reach past K: in the last, partly filled block column it starts early enough
+                    // to end at K, and its values move right by the same amount (the columns it then overlaps with
+                    // an earlier slice stay zero here)
+                    int32_t shift[4] = {0, 0, 0, 0};
+                    for (int32_t t = 0; t < spv; ++t) {
+                        const int64_t k0 = (int64_t)j * b + 32 * t;
+                        const int64_t r0 = std::min<int64_t>(k0, k - 32);
+                        shift[t] = (int32_t)(k0 - r0);
+                        out.slice_rows[4 * c + v * spv + t] = (int32_t)r0;
+                    }
                     if (!real) continue;
                     for (int32_t t = 0; t < R; ++t) {
                         const int32_t br = members[sr * R + t];
@@ -334,8 +343,11 @@ double bcsr_build_composite(const HostBcsr &in, int64_t m, int32_t b, HostBcsr &
                         if (hit == ce || *hit != j) continue;
                         const uint16_t *sb = src + (int64_t)(hit - in.block_col_idx.data()) * b * b;
                         for (int32_t r = 0; r < b; ++r)
-                            std::memcpy(dst + c * 128 * 128 + ((int64_t)t * b + r) * 128 + v * b, sb + (int64_t)r * b,
-                                        (size_t)b * 2);
+                            for (int32_t sl = 0; sl < spv; ++sl) {
+                                if (shift[sl] >= 32) continue;  // the slice lies past K altogether: zeros
+                                std::memcpy(dst + c * 128 * 128 + ((int64_t)t * b + r) * 128 + v * b + 32 * sl + shift[sl],
+                                            sb + (int64_t)r * b + 32 * sl, (size_t)(32 - shift[sl]) * 2);
+                            }
                     }
                 }
                 out.block_col_idx[c] = out.slice_rows[4 * c] / 128;  // the schedule orders block-rows by this

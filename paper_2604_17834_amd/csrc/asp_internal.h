@@ -90,7 +90,7 @@ struct HostWcsr {
 void csr_to_bcsr(int64_t m, int64_t k, const int32_t *row_ptr, const int32_t *col_idx, const void *values,
                  size_t esize, int32_t b_row, int32_t b_col, HostBcsr &out);
 void bcsr_build_schedule(HostBcsr &b);
-double bcsr_build_composite(const HostBcsr &in, int64_t m, int32_t b, HostBcsr &out);
+double bcsr_build_composite(const HostBcsr &in, int64_t m, int64_t k, int32_t b, HostBcsr &out);
 void bcsr_pack_fragments_bf16(const HostBcsr &in, int32_t b_row, int32_t b_col, std::vector<uint8_t> &packed);
 void bcsr_pack_fragments_f32(const HostBcsr &in, int32_t b_row, int32_t b_col, std::vector<uint8_t> &packed);
 bool csr_to_wcsr(int64_t m, int64_t k, const int32_t *row_ptr, const int32_t *col_idx, const void *values,
