@@ -367,7 +367,7 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="bcsr_gate_proj")
-    ap.add_argument("--also", default="wcsr_zipf,bcsr_gate_proj_f32,wcsr_zipf_bf16,bcsr_gate_proj_xt", help="comma list of further workloads reported under 'also' ('' = none)")
+    ap.add_argument("--also", default="wcsr_zipf,bcsr_gate_proj_b64,bcsr_gate_proj_f32,wcsr_zipf_bf16,bcsr_gate_proj_xt", help="comma list of further workloads reported under 'also' ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-reference", action="store_true",
                     help="only run a plain 1 GiB device copy (3 launches): the kernel of known size against "
