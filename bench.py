@@ -45,7 +45,7 @@ def _measured_traffic(workload):
 
 
 _DENSE_MEMO = {}
-SINGLE_LAUNCHES = False   # --single-launches
+SINGLE_LAUNCHES = True    # --no-single-launches switches the second pass off
 WARMUP_MIN_MS = 60.0      # --warmup-min-ms
 
 
@@ -159,7 +159,7 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = _measured_traffic(name)
     roof["kernel_ms_avg"] = kern_ms
-    if per is not None:   # --single-launches
+    if per is not None:   # the second pass ran
         roof["single_launch_ms_median"] = float(np.median(per))
         roof["single_launch_ms_avg"] = float(per.mean())
 
@@ -253,7 +253,8 @@ def run_ablation(args):
         e.update(env)
         steps = min(args.steps, opt.get("max_steps", args.steps))
         cmd = [sys.executable, os.path.abspath(__file__), "--workload", args.workload + opt.get("workload_suffix", ""),
-               "--also", "", "--no-cpu-baseline", "--steps", str(steps), "--warmup", str(min(args.warmup, steps))]
+               "--also", "", "--no-cpu-baseline", "--no-single-launches", "--steps", str(steps),
+               "--warmup", str(min(args.warmup, steps))]
         out = subprocess.run(cmd, env=e, capture_output=True, text=True, timeout=600)
         if out.returncode != 0:
             rows.append({"variant": label, "switches": env, "error": out.stderr[-300:]})
@@ -271,6 +272,8 @@ SWEEP = ["bcsr_sweep_b%d_s%d" % (b, p) for b in (128, 64, 32) for p in (50, 75, 
 
 
 def run_sweep(args, torch, asp, synth):
+    global SINGLE_LAUNCHES
+    SINGLE_LAUNCHES = False
     rows = []
     for name in SWEEP:
         r = run_workload(name, args.steps, args.warmup, torch, asp, synth, False)
@@ -376,8 +379,9 @@ def main():
                     help="time gate, up and down projections of the feed-forward block chained through asp_spmm_xt")
     ap.add_argument("--warmup-min-ms", type=float, default=60.0,
                     help="the untimed warm-up runs at least --warmup calls and at least this long (0: calls only)")
-    ap.add_argument("--single-launches", action="store_true",
-                    help="after the timed region, time the same number of calls one by one (events around each)")
+    ap.add_argument("--no-single-launches", action="store_true",
+                    help="skip the second, untimed pass that times the same number of calls one by one (events around "
+                         "each: median and mean of single launches)")
     ap.add_argument("--sweep", action="store_true",
                     help="the long-prefill BCSR grid (block sizes x sparsities) and the band + long rows WCSR workload at "
                          "both widths: one JSON object, no CPU baseline")
@@ -385,7 +389,7 @@ def main():
                     help="run the BCSR workload once per kernel variant (child processes) and print one JSON object")
     args = ap.parse_args()
     global SINGLE_LAUNCHES, WARMUP_MIN_MS
-    SINGLE_LAUNCHES = args.single_launches
+    SINGLE_LAUNCHES = not args.no_single_launches
     WARMUP_MIN_MS = args.warmup_min_ms
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (one MI355X, no collectives); run with --gpus 1",
