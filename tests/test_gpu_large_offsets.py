@@ -95,14 +95,16 @@ def test_dense_width_two_million_columns(fmt, dtype, b_row, b_col):
         assert not bool(torch.isnan(C).any())
 
 
-def test_xt_two_million_tokens():
+@pytest.mark.parametrize("b", [128, 64])
+def test_xt_two_million_tokens(b):
     # Y: 2^21 tokens x 1152 outputs, X: 2^21 x 640; token rows from 1.7 million on start beyond 2^31 bytes
+    # (64x64 blocks: the same kernel on the composite form)
     m, k, N = 1152, 640, WIDE
-    a = synth.block_sparse_bernoulli(m, k, 128, 128, 0.5, seed=904)
-    print("case xt m", m, "k", k, "tokens", N, flush=True)
+    a = synth.block_sparse_bernoulli(m, k, b, b, 0.5, seed=904)
+    print("case xt b", b, "m", m, "k", k, "tokens", N, flush=True)
     X = _device_normal(N, k, "bf16", seed=905)
     Y = _poisoned(N, m, "bf16")
-    h = asp.asp_create_from_csr("bcsr", "bf16", 128, 128, a.m, a.k, a.row_ptr, a.col_idx, a.values)
+    h = asp.asp_create_from_csr("bcsr", "bf16", b, b, a.m, a.k, a.row_ptr, a.col_idx, a.values)
     try:
         asp.asp_spmm_xt(h, X.data_ptr(), Y.data_ptr(), N, torch.cuda.current_stream().cuda_stream)
         torch.cuda.synchronize()
