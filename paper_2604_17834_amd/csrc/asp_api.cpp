@@ -69,14 +69,15 @@ static asp_status_t create_impl(const asp_config_t *cfg, int64_t m, int64_t k, i
         // times faster; 32x32 blocks, fill 1.60 / 2.09 / 2.73 / 3.21 / 3.77 -> 2.72 / 2.44 / 1.68 / 1.22 / 1.08.
         // With super-rows of neighbouring block-rows (more fill) the break-even was at fill 2.6 / 4.3.
         // ASP_BCSR_COMPOSITE=0/1 is a benchmarking switch.
-        if (cfg->dtype == ASP_DT_BF16 && cfg->b_row < 128 && k >= 32 && h->n_units > 0) {
+        // (128x128 blocks take the same form when K is not a multiple of 128: it keeps every K slice inside K)
+        if (cfg->dtype == ASP_DT_BF16 && (cfg->b_row < 128 || k % 128 != 0) && k >= 32 && h->n_units > 0) {
             static const int env_comp = [] {
                 const char *e = std::getenv("ASP_BCSR_COMPOSITE");
                 return e ? std::atoi(e) : -1;
             }();
             if (env_comp != 0) {
                 h->comp_inflation = bcsr_build_composite(h->hb, m, k, cfg->b_row, h->hc);
-                const double limit = cfg->b_row == 64 ? 2.6 : 4.3;
+                const double limit = cfg->b_row == 128 ? 1.0 : cfg->b_row == 64 ? 2.6 : 4.3;  // 128: no fill
                 h->has_comp = env_comp == 1 || h->comp_inflation <= limit;
                 h->c_n_brows = (int64_t)h->hc.block_row_ptr.size() - 1;
                 h->c_n_units = (int64_t)h->hc.block_col_idx.size();

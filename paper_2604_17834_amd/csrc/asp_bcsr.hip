@@ -296,9 +296,9 @@ BcsrPlan bcsr_plan(const asp_handle *h, int64_t N, bool aligned) {
         // when every compute unit gets at least one tile
         int ncand = 3;
         // (smaller blocks: through the composite form with 128-row super-rows, when the handle has one)
-        if ((h->b_row == 128 || h->has_comp) && N < (1ll << 25)) {
+        if (bcsr_wide_capable(h) && N < (1ll << 25)) {
             const int64_t cus = h->n_cus > 0 ? h->n_cus : 256;
-            const int64_t rows = h->b_row != 128 ? h->hc.n_nonempty : h->hb.n_nonempty > 0 ? h->hb.n_nonempty : h->n_brows;
+            const int64_t rows = h->has_comp ? h->hc.n_nonempty : h->hb.n_nonempty > 0 ? h->hb.n_nonempty : h->n_brows;
             if (rows * ceil_div(N, 512) >= cus) ncand = 4;
         }
         if (env_bn == 64 || env_bn == 128 || env_bn == 256)
@@ -306,7 +306,7 @@ BcsrPlan bcsr_plan(const asp_handle *h, int64_t N, bool aligned) {
         p.bn = choose_bn_weighted(N, cand, cost, ncand);
     }
     p.n_tiles = (int32_t)ceil_div(N, p.bn);
-    p.workgroups = (p.bn == 512 && h->b_row != 128 ? h->c_n_brows : h->n_brows) * p.n_tiles;
+    p.workgroups = (p.bn == 512 && h->has_comp ? h->c_n_brows : h->n_brows) * p.n_tiles;
     return p;
 }
 

@@ -63,8 +63,8 @@ struct WideCfg {
 }  // namespace
 
 // rank_info[r] = {block-row, first stored block, number of stored blocks, block column of the first one} of the r-th
-// block-row of the schedule; only the first n_rows (non-empty) ones are walked.  KAL: K is a multiple of the
-// block size, so no slice of the dense operand reaches past K.
+// block-row of the schedule; only the first n_rows (non-empty) ones are walked.  No slice of the dense operand
+// reaches past K: K is a multiple of the block size, or the blocks come in the composite form (GATHER).
 //
 // XT = false: C[M x N] = A x B, B is K x N row-major (paper, Section II-C).
 // XT = true:  Y[N x M] = X x A^T, X is N x K row-major -- the same product with both dense matrices
@@ -81,9 +81,9 @@ struct WideCfg {
 // block_col_idx then holds, per block, the first dense row of each slice (int4) instead of a block column, the
 // block-row number in rank_info is a super-row number, and piece_rows gives, per super-row, the first row of C of
 // each of the tile's four 32-row pieces (-1: the piece has no rows; its accumulators are zeros).
-// Runs as KAL: the composite form keeps every slice inside K (the slices of a partly filled last block column start
-// early enough to end at K).
-template <bool KAL, bool XT, bool GATHER>
+// The composite form keeps every slice inside K (the slices of a partly filled last block column start early
+// enough to end at K), which is how 128x128 blocks with K % 128 != 0 run here too.
+template <bool XT, bool GATHER>
 __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     const int4 *__restrict__ rank_info, const int32_t *__restrict__ block_col_idx,
     const uint16_t *__restrict__ a_packed, const uint16_t *__restrict__ B, uint16_t *__restrict__ C, int M, int K,
@@ -192,7 +192,6 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     int n_br = 0, n_n0 = 0, n_nb = 0, n_blk0 = 0, n_bcol0 = 0, have_next = 0;  // the tile after it
     uint32_t n_col = 0;  // byte offset of this lane's 16-byte chunk inside a row of B
     int4 n_srow = {0, 0, 0, 0};  // GATHER: dense rows of the four slices of the tile's first block
-    static_assert(!GATHER || KAL, "the composite form keeps every strip inside K");
     auto uniform4 = [&](int4 v) __attribute__((always_inline)) {
         return int4{__builtin_amdgcn_readfirstlane(v.x), __builtin_amdgcn_readfirstlane(v.y),
                     __builtin_amdgcn_readfirstlane(v.z), __builtin_amdgcn_readfirstlane(v.w)};
@@ -230,7 +229,6 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     const uint8_t *pf_abase = nullptr; // next A slice to request
     const uint8_t *pf_bbase = nullptr; // first row of B of the next slice to request
     int pf_n0 = 0;                      // XT: first token of the cursor's tile
-    const uint8_t *pf_xrow0 = nullptr;  // XT: X at (that token, k = 0)
     auto cursor_set_tile = [&](uint32_t colb) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < Cfg::B_LPW; ++i) {
@@ -241,14 +239,10 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
                 int t = 64 * i + xt_token;
                 const int last = N - 1 - (int)colb;
                 t = t < last ? t : last;
-                // (not KAL: the k part is added per request, clamped to the row, from the row's start)
-                pf_voff[i] = (uint32_t)t * (uint32_t)row_bytes + (KAL ? xt_chunk * 16 : 0);
+                pf_voff[i] = (uint32_t)t * (uint32_t)row_bytes + xt_chunk * 16;
             }
         }
-        if (XT) {
-            pf_n0 = __builtin_amdgcn_readfirstlane((int)colb);
-            pf_xrow0 = (const uint8_t *)uniform_ptr((const uint8_t *)B + (int64_t)pf_n0 * row_bytes);
-        }
+        if (XT) pf_n0 = __builtin_amdgcn_readfirstlane((int)colb);
     };
     auto cursor_set_block = [&]() __attribute__((always_inline)) {
         // (made scalar here, well before the requests read them: a memory instruction may read a scalar
@@ -351,22 +345,9 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     auto mfma_drain = [&]() __attribute__((always_inline)) { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); };
 #define ASP_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-    // B row i*NW + wave of the slice at pf_bbase.  Not KAL: rows past K are read from row K-1 (they meet
-    // the zero padding of A's last block column); s = slice inside the block.
-    // XT, not KAL: 16-byte chunks past K are read from the last chunk of the row instead (K % 8 == 0).
-    // The offset counts from the start of the token's row (base pf_xrow0), so it never goes negative.
-    auto xt_voff_edge = [&](int s_, int i) __attribute__((always_inline)) {
-        int kc = pf_bcol * BR + s_ * KS + 8 * xt_chunk;
-        kc = kc < K - 8 ? kc : K - 8;
-        return pf_voff[i] + (uint32_t)kc * 2;
-    };
-#define ASP_B_VOFF(s, i)                                                                                        \
-    (XT ? (KAL ? pf_voff[i] : xt_voff_edge(s, i))                                                              \
-        : (KAL ? pf_voff[i]                                                                                     \
-               : pf_voff[0] + (uint32_t)((((s) * KS + (i) * NW + wave) < K - pf_bcol * BR ? ((s) * KS + (i) * NW) \
-                                                                                           : K - 1 - pf_bcol * BR - wave)) * \
-                                  (uint32_t)row_bytes))
-#define ASP_B_BASE(s) (XT ? (KAL ? pf_bbase : pf_xrow0) : (KAL ? pf_bbase : pf_bbase - (int64_t)(s) * KS * row_bytes))
+    // B row i*NW + wave of the slice at pf_bbase (XT: the slice's 64 bytes of 16 tokens per load)
+#define ASP_B_VOFF(s, i) pf_voff[i]
+#define ASP_B_BASE(s) pf_bbase
     const int64_t slice_step = XT ? (int64_t)KS * 2 : (int64_t)KS * row_bytes;  // next slice of the dense operand
 
     // ---- one step: slice S of a block, in ring buffer S.  The instruction order is fixed by hand
@@ -646,7 +627,7 @@ struct WideOperand {
     const int4 *piece_rows;  // composite: first row of C of each 32-row piece of a super-row
 };
 static WideOperand wide_operand(const asp_handle *h) {
-    if (h->b_row == 128)
+    if (!h->has_comp)
         return WideOperand{(const int4 *)h->d_rank_info, h->d_col_idx,          (const uint16_t *)h->d_values,
                            &h->hb.sorted_weight_prefix,  h->hb.n_nonempty,      h->n_brows,
                            h->n_units,                   false,                 nullptr};
@@ -678,20 +659,19 @@ static void launch_wide(const asp_handle *h, const void *B, void *C, int64_t N, 
     if (!env_xcd)
         for (int x = 1; x <= 8; ++x) runs.start[x] = runs.start[8];
     dim3 grid((unsigned)workers), block(256);
-#define ASP_LAUNCH_WIDE(KAL, GATHER)                                                                                   \
-    hipLaunchKernelGGL((bcsr_spmm_wide_kernel<KAL, XT, GATHER>), grid, block, 0, stream, op.rank_info, op.cols, op.values, \
+#define ASP_LAUNCH_WIDE(GATHER)                                                                                        \
+    hipLaunchKernelGGL((bcsr_spmm_wide_kernel<XT, GATHER>), grid, block, 0, stream, op.rank_info, op.cols, op.values,  \
                        (const uint16_t *)B, (uint16_t *)C, (int)h->m, (int)h->k, (int)N, (int)n_rows, (int)op.n_brows,  \
                        (int)op.n_blocks, n_tiles, group_n, env_xcd, runs, op.piece_rows)
-    if (op.composite) ASP_LAUNCH_WIDE(true, true);  // its slices never reach past K
-    else if (h->k % 128 == 0) ASP_LAUNCH_WIDE(true, false);
-    else ASP_LAUNCH_WIDE(false, false);
+    if (op.composite) ASP_LAUNCH_WIDE(true);
+    else ASP_LAUNCH_WIDE(false);  // K % 128 == 0 (bcsr_wide_capable)
 #undef ASP_LAUNCH_WIDE
 }
 
 // needs 128x128 blocks or the composite form, bn = 512, N % 8 == 0, 8 <= N < 2^25 and 16-byte aligned B and C
 // (the caller checked)
 bool bcsr_wide_launch(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream) {
-    if ((h->b_row != 128 && !h->has_comp) || p.bn != 512) return false;
+    if (!bcsr_wide_capable(h) || p.bn != 512) return false;
     const WideOperand op = wide_operand(h);
     const int64_t n_rows = op.n_rows, n_empty = op.n_brows - n_rows;
     if (n_empty > 0 && n_rows == 0) {  // nothing to multiply: the clearing is all there is
@@ -754,8 +734,8 @@ __global__ __launch_bounds__(256) void bcsr_fill_zero_kernel(uint16_t *__restric
 }
 
 asp_status_t bcsr_spmm_xt_launch(const asp_handle *h, const void *X, void *Y, int64_t N, hipStream_t stream) {
-    const bool wide_ok = h->b_row == 128 || h->has_comp;
-    const int64_t n_rows = h->b_row == 128 || !h->has_comp ? h->hb.n_nonempty : h->hc.n_nonempty;
+    const bool wide_ok = bcsr_wide_capable(h);
+    const int64_t n_rows = !h->has_comp ? h->hb.n_nonempty : h->hc.n_nonempty;
     if (n_rows == 0) {
         hipLaunchKernelGGL(bcsr_fill_zero_kernel, dim3(1024), dim3(256), 0, stream, (uint16_t *)Y, N * h->m);
     } else {

@@ -149,6 +149,8 @@ struct BcsrPlan {
     int64_t workgroups;
 };
 BcsrPlan bcsr_plan(const asp_handle *h, int64_t N, bool aligned);
+// the 128x512-tile kernel can take this handle: 128x128 blocks with K % 128 == 0, or a composite form
+inline bool bcsr_wide_capable(const asp_handle *h) { return h->has_comp || (h->b_row == 128 && h->k % 128 == 0); }
 bool bcsr_dma_launch(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream);
 bool bcsr_f32_launch(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream);
 bool bcsr_wide_launch(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream);
