@@ -228,6 +228,26 @@ def test_plan_follows_tile_width_rule():
         asp.asp_destroy(h)
 
 
+def test_plan_uses_wide_tiles_for_small_blocks_and_ragged_k():
+    # 512-wide tiles need 128-row tiles: 128x128 blocks with K % 128 == 0, or the composite form (smaller blocks
+    # within the fill limit; 128x128 blocks with a partly filled last block column) -- and a tile per compute unit
+    cases = [
+        (128, 40 * 128, 5 * 128, 0.5, 512),        # plain
+        (128, 40 * 128, 5 * 128 + 24, 0.5, 512),   # ragged K: composite form without grouping
+        (64, 40 * 128, 5 * 128 + 24, 0.5, 512),
+        (32, 40 * 128, 5 * 128, 0.5, 512),
+        (32, 40 * 128, 16, 0.0, 256),              # K below one slice: no composite form
+        (64, 10 * 128, 5 * 128, 0.5, 256),         # too few tiles for every compute unit
+    ]
+    for b, m, k, sparsity, want in cases:
+        a = synth.block_sparse_bernoulli(m, k, b, b, sparsity, 11)
+        h = asp.asp_create_from_csr("bcsr", "bf16", b, b, a.m, a.k, a.row_ptr, a.col_idx, a.values, flags=HOST)
+        try:
+            assert asp.asp_plan_spmm(h, 4096).bn == want, (b, m, k)
+        finally:
+            asp.asp_destroy(h)
+
+
 def test_dense_width_limit_is_the_headers_and_is_enforced():
     hdr = open(os.path.join(os.path.dirname(__file__), "..", "include", "asyncsparse.h")).read()
     mm = re.search(r"#define ASP_MAX_N \((\d+)ll \* (\d+)\)", hdr)
