@@ -169,22 +169,30 @@ __global__ __launch_bounds__(256) void wcsr16_spmm_kernel(const int4 *__restrict
         float4 b[D][2][NG];
     };
     const int tile0 = td.y >> 3, tile1 = td.z >> 3;
+    // Which packed column a lane multiplies in which k step is free as long as A and B agree: lane group kq takes
+    // columns 2 kq and 2 kq + 1 of a tile (k steps h = 0, 1), so its two indices and its two values of a row are
+    // one 8-byte load each and the 16 x 4 lanes read a tile's 512 bytes of values as one contiguous span.
     auto load_idx = [&](int base, int (&idx)[D][2]) {
 #pragma unroll
-        for (int d = 0; d < D; ++d)
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-                idx[d][h] = base + d < tile1 ? window_col_idx[(base + d) * 8 + 4 * h + kq] : -1;
+        for (int d = 0; d < D; ++d) {
+            int2 c2 = make_int2(-1, -1);
+            if (base + d < tile1) c2 = *(const int2 *)(window_col_idx + (int64_t)(base + d) * 8 + 2 * kq);
+            idx[d][0] = c2.x;
+            idx[d][1] = c2.y;
+        }
     };
     auto gather = [&](int base, const int (&idx)[D][2], Chunk &c) {
 #pragma unroll
-        for (int d = 0; d < D; ++d)
+        for (int d = 0; d < D; ++d) {
+            float2 a2 = make_float2(0.f, 0.f);
+            if (base + d < tile1) a2 = *(const float2 *)(values + (int64_t)(base + d) * 128 + jl * 8 + 2 * kq);
+            c.a[d][0] = a2.x;
+            c.a[d][1] = a2.y;
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                c.a[d][h] = base + d < tile1 ? values[(int64_t)(base + d) * 128 + jl * 8 + 4 * h + kq] : 0.f;
+            for (int h = 0; h < 2; ++h)
 #pragma unroll
                 for (int g = 0; g < NG; ++g) c.b[d][h][g] = gather4(B, idx[d][h], N, n0 + 64 * g, VEC);
-            }
+        }
     };
     auto multiply = [&](int base, const Chunk &c) {
 #pragma unroll
@@ -259,15 +267,22 @@ __global__ __launch_bounds__(256) void wcsr32_spmm_kernel(const int4 *__restrict
         float a[4][MTW];
         float4 b[4];
     };
+    // lane group kq takes packed columns 4 kq .. 4 kq + 3 of a tile (k steps h = 0..3; any assignment works as long
+    // as A and B agree): its four indices and its four values of a row are one 16-byte load each, and the 32 x 2
+    // lanes read the 1 KB of values of a row tile as one contiguous span
     auto fetch = [&](int tile, Stage &s) {
+        const int4 c4 = *(const int4 *)(window_col_idx + (int64_t)tile * 8 + 4 * kq);
+        const int col[4] = {c4.x, c4.y, c4.z, c4.w};
 #pragma unroll
-        for (int h = 0; h < 4; ++h) {
-            const int col = window_col_idx[tile * 8 + 2 * h + kq];
-#pragma unroll
-            for (int i = 0; i < MTW; ++i)
-                s.a[h][i] = values[(int64_t)tile * (BRW * 8) + (i * 32 + jl) * 8 + 2 * h + kq];
-            s.b[h] = gather4(B, col, N, n0, VEC);
+        for (int i = 0; i < MTW; ++i) {
+            const float4 a4 = *(const float4 *)(values + (int64_t)tile * (BRW * 8) + (i * 32 + jl) * 8 + 4 * kq);
+            s.a[0][i] = a4.x;
+            s.a[1][i] = a4.y;
+            s.a[2][i] = a4.z;
+            s.a[3][i] = a4.w;
         }
+#pragma unroll
+        for (int h = 0; h < 4; ++h) s.b[h] = gather4(B, col[h], N, n0, VEC);
     };
     auto multiply = [&](const Stage &s) {
 #pragma unroll
