@@ -240,7 +240,7 @@ __global__ __launch_bounds__(256) void wcsr16_spmm_kernel(const int4 *__restrict
 // lane l: kq = l / 32 picks one of 2 packed columns of a k step, jl = l % 32 is the MFMA N index;
 // the wave covers 128 columns.  MTW = window height / 32 MFMA row tiles share every gathered B value.
 template <int MTW, bool VEC>
-__global__ __launch_bounds__(256) void wcsr32_spmm_kernel(const int4 *__restrict__ tasks, int n_tasks,
+__global__ __launch_bounds__(256, 2) void wcsr32_spmm_kernel(const int4 *__restrict__ tasks, int n_tasks,
                                                           const int32_t *__restrict__ window_col_idx,
                                                           const float *__restrict__ values,
                                                           const float *__restrict__ B, float *__restrict__ C, int M,
@@ -297,12 +297,18 @@ __global__ __launch_bounds__(256) void wcsr32_spmm_kernel(const int4 *__restrict
     };
 
     const int tile0 = td.y >> 3, tile1 = td.z >> 3;
-    Stage cur, nxt;
-    fetch(tile0, cur);
-    for (int tile = tile0; tile < tile1; ++tile) {
-        if (tile + 1 < tile1) fetch(tile + 1, nxt);
-        multiply(cur);
-        if (tile + 1 < tile1) cur = nxt;
+    // two tiles in flight while a third is multiplied (three stages, walked with fixed register names): at this
+    // register count the occupancy is the same as with one tile in flight, and the gather needs the bytes in flight
+    Stage s0, s1, s2;
+    fetch(tile0, s0);
+    if (tile0 + 1 < tile1) fetch(tile0 + 1, s1);
+    for (int tile = tile0; tile < tile1; tile += 3) {
+        if (tile + 2 < tile1) fetch(tile + 2, s2);
+        multiply(s0);
+        if (tile + 3 < tile1) fetch(tile + 3, s0);
+        if (tile + 1 < tile1) multiply(s1);
+        if (tile + 4 < tile1) fetch(tile + 4, s1);
+        if (tile + 2 < tile1) multiply(s2);
     }
 
     // D layout: register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, MFMA column l%32
