@@ -146,6 +146,23 @@ asp_status_t asp_spmm(const asp_handle_t *h, const void *B, void *C, int64_t N, 
 asp_status_t asp_reserve(asp_handle_t *h, int64_t N);
 
 /*
+ * asp_spmm for callers that cannot allocate at all -- code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc -- and therefore cannot call asp_reserve either.  Same arguments, same result (bit for bit
+ * that of asp_spmm on a handle with reserved scratch), but the fp32 partial tiles of split WCSR windows go into a
+ * scratch array that is part of the library's device image (ASP_STATIC_SCRATCH_BYTES on every GPU the library
+ * runs on, held until the process ends) instead of a buffer from asp_reserve.  Calls no hipMalloc, hipFree or other
+ * allocating routine; its one piece of set-up, looking up the array's device address, happens when a WCSR handle with split
+ * windows is created.  Returns ASP_ERR_BUFFER_TOO_SMALL when the handle's split tasks need more than the array
+ * holds at this N (4 * b_row * N bytes per task of a split window): nothing is launched then.  BCSR handles and
+ * WCSR handles without split windows use no scratch and run exactly as in asp_spmm.
+ * Every call on one GPU shares that GPU's array, whatever the handle: calls that overlap in time on one GPU race
+ * (order them on one stream, or with events).  Nothing in the array has to start at zero -- every slot a call
+ * reads was written by that call first -- so contents left by earlier calls do no harm.
+ */
+#define ASP_STATIC_SCRATCH_BYTES (64ull << 20)
+asp_status_t asp_spmm_static_scratch(const asp_handle_t *h, const void *B, void *C, int64_t N, void *stream);
+
+/*
  * Y = X x A^T with K-contiguous dense operands: the same product as asp_spmm with B = X^T and C = Y^T, in
  * the layout of the paper's LLM case study (Section IV-D: C = W X^T, activations stored tokens x hidden),
  * so that projections can be chained without transposes.

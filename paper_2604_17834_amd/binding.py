@@ -28,7 +28,7 @@ _DT = {"bf16": ASP_DT_BF16, "f32": ASP_DT_F32}
 _NP = {ASP_DT_BF16: np.uint16, ASP_DT_F32: np.float32}
 
 EXPORTED_SYMBOLS = [
-    "asp_create_from_csr", "asp_spmm", "asp_spmm_xt", "asp_reserve", "asp_rcm", "asp_permute_csr",
+    "asp_create_from_csr", "asp_spmm", "asp_spmm_static_scratch", "asp_spmm_xt", "asp_reserve", "asp_rcm", "asp_permute_csr",
     "asp_mtx_read", "asp_mtx_get", "asp_mtx_free", "asp_probe_mfma", "asp_probe_read", "asp_get_info", "asp_plan_spmm", "asp_export", "asp_destroy",
     "asp_status_string", "asp_last_error",
 ]
@@ -79,6 +79,8 @@ def lib() -> ctypes.CDLL:
     L.asp_create_from_csr.restype = ctypes.c_int
     L.asp_spmm.argtypes = [vp, vp, vp, i64, vp]
     L.asp_spmm.restype = ctypes.c_int
+    L.asp_spmm_static_scratch.argtypes = [vp, vp, vp, i64, vp]
+    L.asp_spmm_static_scratch.restype = ctypes.c_int
     L.asp_spmm_xt.argtypes = [vp, vp, vp, i64, vp]
     L.asp_spmm_xt.restype = ctypes.c_int
     L.asp_reserve.argtypes = [vp, i64]
@@ -142,6 +144,17 @@ def asp_spmm(handle, B_ptr, C_ptr, N, stream=None, check=True):
     st = lib().asp_spmm(handle, B_ptr, C_ptr, N, stream)
     if check and st != ASP_OK:
         raise AspError(st, "asp_spmm")
+    return st
+
+
+ASP_STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def asp_spmm_static_scratch(handle, B_ptr, C_ptr, N, stream=None, check=True):
+    """asp_spmm for callers that cannot allocate: split WCSR windows use the library's static scratch array."""
+    st = lib().asp_spmm_static_scratch(handle, B_ptr, C_ptr, N, stream)
+    if check and st != ASP_OK:
+        raise AspError(st, "asp_spmm_static_scratch")
     return st
 
 

@@ -142,6 +142,12 @@ static asp_status_t create_impl(const asp_config_t *cfg, int64_t m, int64_t k, i
     if ((s = upload(&h->d_zero_windows, h->hw.zero_windows.data(), h->hw.zero_windows.size() * 4, stream))) return s;
     if ((s = upload(&h->d_ws_slot, h->hw.ws_slot.data(), h->hw.ws_slot.size() * 4, stream))) return s;
     if ((s = wcsr_build_tasks_device(h, stream))) return s;  // wavefront-scan partition on the GPU
+    if (h->n_split_tasks > 0) {
+        // set-up for asp_spmm_static_scratch: the device address of the static scratch array, once per device
+        float *p = nullptr;
+        int64_t n = 0;
+        if ((s = wcsr_static_scratch(h->device, &p, &n))) return s;
+    }
     ASP_HIP_TRY(hipStreamSynchronize(stream));
     // the device arrays are the canonical ones; drop the host copies (values can be gigabytes)
     h->hw = HostWcsr();
@@ -220,7 +226,28 @@ asp_status_t asp_spmm(const asp_handle_t *h, const void *B, void *C, int64_t N, 
     if (N > ASP_MAX_N || h->m * N >= (1ll << 40)) return fail(ASP_ERR_UNSUPPORTED, "N too large (ASP_MAX_N, and M x N below 2^40)");
     if (asp_status_t s = check_current_device(h)) return s;
     if (h->format == ASP_FMT_BCSR) return bcsr_spmm_launch(h, B, C, N, (hipStream_t)stream);
-    return wcsr_spmm_launch(h, B, C, N, (hipStream_t)stream);
+    return wcsr_spmm_launch(h, B, C, N, h->d_ws, h->ws_floats, (hipStream_t)stream);
+}
+
+asp_status_t asp_spmm_static_scratch(const asp_handle_t *h, const void *B, void *C, int64_t N, void *stream) {
+    if (!h || !B || !C) return fail(ASP_ERR_INVALID_ARG, "null handle, B or C");
+    if (N < 1) return fail(ASP_ERR_INVALID_ARG, "N must be >= 1");
+    if (h->device < 0) return fail(ASP_ERR_UNSUPPORTED, "handle was converted on the host only; it has no device arrays");
+    if (N > ASP_MAX_N || h->m * N >= (1ll << 40)) return fail(ASP_ERR_UNSUPPORTED, "N too large (ASP_MAX_N, and M x N below 2^40)");
+    if (asp_status_t s = check_current_device(h)) return s;
+    if (h->format == ASP_FMT_BCSR) return bcsr_spmm_launch(h, B, C, N, (hipStream_t)stream);  // uses no scratch
+    float *ws = nullptr;
+    int64_t ws_floats = 0;
+    if (h->n_split_tasks > 0) {
+        const int64_t need = wcsr_scratch_floats(h, N);
+        if (need > (int64_t)(ASP_STATIC_SCRATCH_BYTES / sizeof(float)))
+            return fail(ASP_ERR_BUFFER_TOO_SMALL,
+                        "the partial tiles of this handle's split windows at this N take " + std::to_string(need * 4) +
+                            " bytes, the static scratch holds " + std::to_string((long long)ASP_STATIC_SCRATCH_BYTES) +
+                            ": use asp_reserve + asp_spmm");
+        if (asp_status_t s = wcsr_static_scratch(h->device, &ws, &ws_floats)) return s;  // resolved at creation: no HIP call
+    }
+    return wcsr_spmm_launch(h, B, C, N, ws, ws_floats, (hipStream_t)stream);
 }
 
 asp_status_t asp_reserve(asp_handle_t *h, int64_t N) {

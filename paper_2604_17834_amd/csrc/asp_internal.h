@@ -166,13 +166,20 @@ struct WcsrPlan {
     int64_t workgroups;
 };
 WcsrPlan wcsr_plan(const asp_handle *h, int64_t N, bool aligned);
-asp_status_t wcsr_spmm_launch(const asp_handle *h, const void *B, void *C, int64_t N, hipStream_t stream);
-asp_status_t wcsr_bf16_spmm_launch(const asp_handle *h, const void *B, void *C, int64_t N, hipStream_t stream);
+// ws / ws_floats: the fp32 buffer that takes the partial tiles of split windows and its capacity (the handle's
+// reserved buffer, or the library's static one; nullptr / 0: none)
+asp_status_t wcsr_spmm_launch(const asp_handle *h, const void *B, void *C, int64_t N, float *ws, int64_t ws_floats,
+                              hipStream_t stream);
+asp_status_t wcsr_bf16_spmm_launch(const asp_handle *h, const void *B, void *C, int64_t N, float *ws, int64_t ws_floats,
+                                   hipStream_t stream);
+// The library's static scratch array on `device` (which must be the current device): its device address, resolved
+// once per device, and its capacity in floats.
+asp_status_t wcsr_static_scratch(int device, float **ptr, int64_t *floats);
 int64_t wcsr_scratch_floats(const asp_handle *h, int64_t N);  // fp32 scratch elements a call of width N uses
 // clears the C rows of windows without columns (keep_split: and leaves split windows alone; else clears them too)
 void wcsr_clear_empty_windows(const asp_handle *h, void *C, int64_t N, bool keep_split, hipStream_t stream);
 // rows of split windows = sum of their tasks' partial tiles, in task order
-void wcsr_sum_partial_tiles(const asp_handle *h, void *C, int64_t N, hipStream_t stream);
+void wcsr_sum_partial_tiles(const asp_handle *h, void *C, int64_t N, const float *ws, hipStream_t stream);
 // GPU task partition: fills h->d_tasks / h->n_tasks from h->d_row_ptr (wavefront scans)
 asp_status_t wcsr_build_tasks_device(asp_handle *h, hipStream_t stream);
 }  // namespace asp

@@ -15,10 +15,37 @@
 // 16 or 32 rows tall, so heights 16 (default), 32 and 64 are built.
 #include <algorithm>
 #include <cstdlib>
+#include <mutex>
 
 #include "asp_internal.h"
 
+// Scratch for callers that cannot allocate (asp_spmm_static_scratch): the partial tiles of split windows go here
+// instead of into a buffer from asp_reserve.  Every GPU the library runs on holds its own copy at its own address
+// until the process ends.  In host code this name is only a handle for hipGetSymbolAddress; kernels and copies get
+// the device address that wcsr_static_scratch() resolved.
+static __device__ __align__(256) float scratch[ASP_STATIC_SCRATCH_BYTES / sizeof(float)];
+
 namespace asp {
+
+asp_status_t wcsr_static_scratch(int device, float **ptr, int64_t *floats) {
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex mu;
+    static float *resolved[MAX_DEVICES] = {};
+    if (device < 0 || device >= MAX_DEVICES) return fail(ASP_ERR_UNSUPPORTED, "device index beyond the static scratch table");
+    std::lock_guard<std::mutex> lock(mu);
+    if (!resolved[device]) {
+        int cur = -1;
+        ASP_HIP_TRY(hipGetDevice(&cur));
+        if (cur != device) return fail(ASP_ERR_INVALID_ARG, "the static scratch of a device is resolved with that device current");
+        float *p = nullptr;
+        ASP_HIP_TRY(hipGetSymbolAddress((void **)&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(ASP_ERR_HIP, "hipGetSymbolAddress returned no address for the static scratch");
+        resolved[device] = p;
+    }
+    *ptr = resolved[device];
+    *floats = (int64_t)(ASP_STATIC_SCRATCH_BYTES / sizeof(float));
+    return ASP_OK;
+}
 
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
@@ -503,14 +530,14 @@ void wcsr_clear_empty_windows(const asp_handle *h, void *C, int64_t N, bool keep
                        vec);
 }
 
-void wcsr_sum_partial_tiles(const asp_handle *h, void *C, int64_t N, hipStream_t stream) {
+void wcsr_sum_partial_tiles(const asp_handle *h, void *C, int64_t N, const float *ws, hipStream_t stream) {
     if (h->n_split_tasks == 0) return;
     const bool vec = N % 4 == 0 && ((uintptr_t)C & 15) == 0;
     const unsigned gy = (unsigned)std::min<int64_t>(64, ceil_div((int64_t)h->b_row * N, vec ? 1024 : 256));
     dim3 grid((unsigned)h->n_zero_windows, gy), block(256);
 #define ASP_SUM(T, U)                                                                                              \
     hipLaunchKernelGGL((wcsr_sum_partials_kernel<T, U>), grid, block, 0, stream, h->d_zero_windows, h->d_ws_slot, \
-                       h->d_row_ptr, h->task_cols, h->b_row, (T *)C, h->d_ws, (int)h->m, N)
+                       h->d_row_ptr, h->task_cols, h->b_row, (T *)C, ws, (int)h->m, N)
     if (h->dtype == ASP_DT_BF16) {
         if (vec) ASP_SUM(__bf16, 4);
         else ASP_SUM(__bf16, 1);
@@ -521,15 +548,16 @@ void wcsr_sum_partial_tiles(const asp_handle *h, void *C, int64_t N, hipStream_t
 #undef ASP_SUM
 }
 
-asp_status_t wcsr_spmm_launch(const asp_handle *h, const void *B, void *C, int64_t N, hipStream_t stream) {
-    if (h->dtype == ASP_DT_BF16) return wcsr_bf16_spmm_launch(h, B, C, N, stream);
+asp_status_t wcsr_spmm_launch(const asp_handle *h, const void *B, void *C, int64_t N, float *ws_buf, int64_t ws_floats,
+                              hipStream_t stream) {
+    if (h->dtype == ASP_DT_BF16) return wcsr_bf16_spmm_launch(h, B, C, N, ws_buf, ws_floats, stream);
     const bool aligned = (((uintptr_t)B | (uintptr_t)C) & 15) == 0;
     const WcsrPlan p = wcsr_plan(h, N, aligned);
     const bool vec = p.vectorized != 0;
     if (p.workgroups >= (1ll << 31)) return fail(ASP_ERR_UNSUPPORTED, "too many wave tasks");
     // split windows: partial tiles in the scratch buffer when it is large enough, else atomic adds into C
-    const bool partial = h->n_split_tasks > 0 && h->ws_floats >= wcsr_scratch_floats(h, N);
-    float *ws = partial ? h->d_ws : nullptr;
+    const bool partial = h->n_split_tasks > 0 && ws_buf && ws_floats >= wcsr_scratch_floats(h, N);
+    float *ws = partial ? ws_buf : nullptr;
     wcsr_clear_empty_windows(h, C, N, partial, stream);
     if (h->n_tasks > 0) {
         dim3 grid((unsigned)p.workgroups), block(256);
@@ -568,7 +596,7 @@ asp_status_t wcsr_spmm_launch(const asp_handle *h, const void *B, void *C, int64
 #undef ASP_W16
 #undef ASP_W32
     }
-    if (partial) wcsr_sum_partial_tiles(h, C, N, stream);
+    if (partial) wcsr_sum_partial_tiles(h, C, N, ws, stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(ASP_ERR_HIP, std::string("WCSR kernel launch: ") + hipGetErrorString(e));
     return ASP_OK;

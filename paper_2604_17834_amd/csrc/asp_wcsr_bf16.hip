@@ -195,7 +195,8 @@ __global__ __launch_bounds__(64) void wcsr_bf16_generic_kernel(const int32_t *__
 }
 
 // ---- host side ------------------------------------------------------------------------------------
-asp_status_t wcsr_bf16_spmm_launch(const asp_handle *h, const void *B, void *C, int64_t N, hipStream_t stream) {
+asp_status_t wcsr_bf16_spmm_launch(const asp_handle *h, const void *B, void *C, int64_t N, float *ws, int64_t ws_floats,
+                                   hipStream_t stream) {
     const bool aligned = (((uintptr_t)B | (uintptr_t)C) & 15) == 0;
     const WcsrPlan p = wcsr_plan(h, N, aligned);
     const uint16_t *vals = (const uint16_t *)h->d_values, *Bh = (const uint16_t *)B;
@@ -211,7 +212,7 @@ asp_status_t wcsr_bf16_spmm_launch(const asp_handle *h, const void *B, void *C, 
         }
     } else {
         if (p.workgroups >= (1ll << 31)) return fail(ASP_ERR_UNSUPPORTED, "too many wave tasks");
-        if (h->n_split_tasks > 0 && h->ws_floats < wcsr_scratch_floats(h, N))
+        if (h->n_split_tasks > 0 && ws_floats < wcsr_scratch_floats(h, N))
             return fail(ASP_ERR_BUFFER_TOO_SMALL,
                         "bf16 WCSR with split windows needs scratch memory for this width: call asp_reserve(handle, N) first");
         wcsr_clear_empty_windows(h, C, N, true, stream);
@@ -221,13 +222,13 @@ asp_status_t wcsr_bf16_spmm_launch(const asp_handle *h, const void *B, void *C, 
             const int nt = (int)h->n_tasks;
 #define ASP_WB(MTW)                                                                                                 \
     hipLaunchKernelGGL((wcsr_bf16_spmm_kernel<MTW>), grid, block, 0, stream, tasks, nt, h->d_col_idx, vals, Bh, Ch, \
-                       h->d_ws, h->d_ws_slot, h->d_row_ptr, h->task_cols, M, N, p.n_tiles)
+                       ws, h->d_ws_slot, h->d_row_ptr, h->task_cols, M, N, p.n_tiles)
             if (h->b_row == 16) ASP_WB(1);
             else if (h->b_row == 32) ASP_WB(2);
             else ASP_WB(4);
 #undef ASP_WB
         }
-        wcsr_sum_partial_tiles(h, C, N, stream);
+        wcsr_sum_partial_tiles(h, C, N, ws, stream);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(ASP_ERR_HIP, std::string("WCSR bf16 kernel launch: ") + hipGetErrorString(e));
