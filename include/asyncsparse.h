@@ -171,8 +171,8 @@ asp_status_t asp_spmm_static_scratch(const asp_handle_t *h, const void *B, void 
  * Asynchronous, never synchronises, never allocates.  fp32 accumulation, round-to-nearest-even to bf16;
  * bitwise reproducible.  128x128 blocks (and 64x64 / 32x32 blocks when k >= 32 and grouping their block-rows
  * into 128-row tiles adds at most 2.6x / 4.3x zero fill) with k % 8 == 0,
- * m % 8 == 0, 16-byte aligned X and Y and at least one 128 x 512 tile per compute unit run on the matrix
- * cores; everything else takes a slow generic kernel.
+ * m % 8 == 0 and 16-byte aligned X and Y run on the matrix cores (128 outputs x 512 tokens per workgroup);
+ * everything else takes a slow generic kernel.
  */
 asp_status_t asp_spmm_xt(const asp_handle_t *h, const void *X, void *Y, int64_t N, void *stream);
 

@@ -740,15 +740,17 @@ asp_status_t bcsr_spmm_xt_launch(const asp_handle *h, const void *X, void *Y, in
         hipLaunchKernelGGL(bcsr_fill_zero_kernel, dim3(1024), dim3(256), 0, stream, (uint16_t *)Y, N * h->m);
     } else {
         const bool aligned = (((uintptr_t)X | (uintptr_t)Y) & 15) == 0;
-        const int64_t cus = h->n_cus > 0 ? h->n_cus : 256;
         const int64_t n_tiles = ceil_div(N, 512);
         // benchmarking switch only: ASP_BCSR_XT=generic forces the fallback
         static const bool force_generic = [] {
             const char *e = std::getenv("ASP_BCSR_XT");
             return e && std::strcmp(e, "generic") == 0;
         }();
+        // (no lower bound on the number of tiles: with fewer 128 x 512 tiles than compute units part of the chip
+        // idles, which still is two orders of magnitude faster than the generic kernel -- the down projection of
+        // the case study has 28 block-rows and would need 4600 tokens to give every compute unit a tile)
         if (!force_generic && wide_ok && aligned && h->k % 8 == 0 && h->m % 8 == 0 && N < (1ll << 25) &&
-            h->k < (1ll << 22) && n_rows * n_tiles >= cus) {
+            h->k < (1ll << 22)) {
             launch_wide<true>(h, X, Y, N, (int)n_tiles, stream);
         } else {
             dim3 grid((unsigned)h->n_brows, (unsigned)ceil_div(N, 64)), block(256);

@@ -375,6 +375,30 @@ def test_bcsr_xt_generic_path_parity(b, m, k, N, misalign):
     check_against_oracle(a, np.ascontiguousarray(X.T), np.ascontiguousarray(Y.T))
 
 
+@pytest.mark.parametrize("b,m,k,N", [
+    (128, 256, 256, 64),        # 2 tiles: fewer than the 8 workgroups the launch never goes below
+    (128, 128, 384, 8),         # one tile, 8 tokens
+    (64, 640, 320, 200),        # smaller blocks on 128-row stacks, a token tail
+    (128, 28 * 128, 1024, 1032),  # 28 block-rows x 3 token tiles, the last one 8 tokens wide
+])
+def test_bcsr_xt_matrix_core_path_with_fewer_tiles_than_compute_units(b, m, k, N):
+    a = synth.block_sparse_bernoulli(m, k, b, b, 0.5, seed=48 + N, dtype="bf16")
+    X = synth.dense_normal(N, k, "bf16", seed=49)
+    Y = gpu_spmm_xt(a, b, X)
+    check_against_oracle(a, np.ascontiguousarray(X.T), np.ascontiguousarray(Y.T))
+
+
+@pytest.mark.parametrize("N", [1024, 4096])
+def test_bcsr_xt_down_projection_at_short_sequences(N):
+    # the case study's down projection (3584 x 18944, 28 block-rows) at sequence lengths where it has fewer
+    # 128 x 512 tiles than the chip has compute units: still the matrix-core path
+    a, fmt, br, bc, _, dt, seedB = synth.workload("bcsr_down_proj")
+    X = synth.dense_normal(N, a.k, dt, seedB + N)
+    Y = gpu_spmm_xt(a, br, X)
+    tok = _sample_columns(N, 256, np.random.default_rng(6))
+    check_against_oracle(a, np.ascontiguousarray(X[tok].T), np.ascontiguousarray(Y[tok].T))
+
+
 def test_bcsr_xt_equals_transposed_spmm_bitwise():
     # both entries run the same multiply-add sequence per output on the matrix cores
     m, k, N = 48 * 128, 6 * 128, 4096
