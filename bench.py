@@ -58,7 +58,23 @@ def _dense_normal(synth, rows, cols, dt, seed):
     return _DENSE_MEMO[key]
 
 
-def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
+_CSR_MEMO = {}
+
+
+def _workload(synth, name):
+    """synth.workload, keeping the last matrix: "<name>_n<width>" variants reuse the matrix of "<name>"."""
+    import re
+    base = re.sub(r"_n\d+", "", name)
+    if base not in _CSR_MEMO:
+        _CSR_MEMO.clear()
+        _CSR_MEMO[base] = synth.workload(base)
+    w = list(_CSR_MEMO[base])
+    if base != name:
+        w[4] = synth.workload_width(name)
+    return tuple(w)
+
+
+def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline, cpu_seconds=15.0):
     import numpy as np
 
     t0 = time.time()
@@ -66,7 +82,7 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
     xt = name.endswith("_xt")
     # "<workload>_rcm": the matrix goes through the library's Reverse Cuthill-McKee reordering first (Section IV-A)
     rcm = name.endswith("_rcm")
-    a, fmt, b_row, b_col, N, dt, seedB = synth.workload(name[:-3] if xt else name[:-4] if rcm else name)
+    a, fmt, b_row, b_col, N, dt, seedB = _workload(synth, name[:-3] if xt else name[:-4] if rcm else name)
     t_reorder = None
     if rcm:
         t1 = time.time()
@@ -74,7 +90,11 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
         rp, ci, va = asp.asp_permute_csr(a.m, a.k, a.row_ptr, a.col_idx, a.values, dt, perm, perm)
         a = synth.Csr(a.m, a.k, rp, ci, va, dt)
         t_reorder = time.time() - t1
-    B = _dense_normal(synth, N, a.k, dt, seedB) if xt else _dense_normal(synth, a.k, N, dt, seedB)
+    # the dense operand: drawn on the host (numpy, seeded) up to 2^27 elements, beyond that on the device (torch
+    # generator, seeded) -- a 1 GB operand takes a minute on the host; the oracle always gets the device's bits
+    shape = (N, a.k) if xt else (a.k, N)
+    on_device = shape[0] * shape[1] > (1 << 27)
+    B = None if on_device else _dense_normal(synth, shape[0], shape[1], dt, seedB)
     t_gen = time.time() - t0
     spmm = asp.asp_spmm_xt if xt else asp.asp_spmm
 
@@ -88,12 +108,15 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
     # handles run at the same speed with it and are bitwise reproducible; nothing is allocated for other handles
     asp.asp_reserve(h, N)
 
-    if dt == "bf16":
-        Bd = torch.from_numpy(B.view(np.int16)).cuda()
-        Cd = torch.empty((N, a.m) if xt else (a.m, N), dtype=torch.int16, device="cuda")
+    if on_device:
+        g = torch.Generator(device="cuda")
+        g.manual_seed(seedB)
+        Bd = torch.randn(shape, dtype=torch.bfloat16 if dt == "bf16" else torch.float32, device="cuda", generator=g)
+        if dt == "bf16":
+            Bd = Bd.view(torch.int16)
     else:
-        Bd = torch.from_numpy(B).cuda()
-        Cd = torch.empty((N, a.m) if xt else (a.m, N), dtype=torch.float32, device="cuda")
+        Bd = torch.from_numpy(B.view(np.int16) if dt == "bf16" else B).cuda()
+    Cd = torch.empty((N, a.m) if xt else (a.m, N), dtype=torch.int16 if dt == "bf16" else torch.float32, device="cuda")
     bp, cp = Bd.data_ptr(), Cd.data_ptr()
 
     # untimed warm-up: `warmup` calls, and at least WARMUP_MIN_MS of them -- the GPU takes about 30 ms under load to
@@ -167,7 +190,8 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
         "workload": name, "format": fmt, "dtype": dt, "b_row": b_row, "b_col": b_col, "m": a.m, "k": a.k, "N": N, "nnz": a.nnz,
         "fill_ratio": info.fill_ratio, "bn": plan.bn, "workgroups": int(plan.workgroups),
         "value": flops_eff / (wall_ms * 1e-3) / 1e9, "ms_per_step": wall_ms, "roofline": roof,
-        "convert_s": t_convert, "generate_s": t_gen, "warmup_calls_run": warm_run, **extra,
+        "convert_s": t_convert, "generate_s": t_gen, "warmup_calls_run": warm_run,
+        "dense_operand_drawn_on": "device" if on_device else "host", **extra,
     }
     if t_reorder is not None:
         res["reorder_s"] = t_reorder
@@ -199,13 +223,18 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline):
         import oracle
         # bounded sample: the oracle on a slice of B's columns (column j of C needs column j of B only)
         probe = min(N, 16)
+
+        def first_columns(n):   # the oracle's operand is k x n: the first n columns (xt: tokens) as the GPU has them
+            sl = Bd[:n].T if xt else Bd[:, :n]
+            h = sl.contiguous().cpu().numpy()
+            return h.view(np.uint16) if dt == "bf16" else h
+        Bp = first_columns(probe)
         t0 = time.perf_counter()
-        Bo = np.ascontiguousarray(B.T) if xt else B  # the oracle's operand is k x N
-        oracle.spmm(a.m, a.k, a.row_ptr, a.col_idx, a.values, dt, np.ascontiguousarray(Bo[:, :probe]))
+        oracle.spmm(a.m, a.k, a.row_ptr, a.col_idx, a.values, dt, Bp)
         tp = time.perf_counter() - t0
-        ncols = int(max(probe, min(N, 15.0 / max(tp / probe, 1e-9))))
+        ncols = int(max(probe, min(N, cpu_seconds / max(tp / probe, 1e-9))))
         ncols = max(16, ncols // 16 * 16) if N >= 16 else N
-        Bs = np.ascontiguousarray(Bo[:, :ncols])
+        Bs = first_columns(ncols)
         t0 = time.perf_counter()
         ref, S = oracle.spmm(a.m, a.k, a.row_ptr, a.col_idx, a.values, dt, Bs)
         tc = time.perf_counter() - t0
@@ -287,20 +316,21 @@ def run_sweep(args, torch, asp, synth):
     print(json.dumps({"sweep": rows, "steps": args.steps, "warmup": args.warmup}))
 
 
-def box_peaks(torch, asp):
+def box_peaks(torch):
     """What this machine sustains, beside the published peaks: matrix-core rate of an MFMA-only loop (both dtypes) and
     the bandwidth of a plain 1 GiB device copy (read + write), of a 1 GiB fill (write only) and of a read-only stream over 1 GiB."""
+    from paper_2604_17834_amd import measure   # probe kernels in a library of their own, not the product's
     stream = torch.cuda.current_stream().cuda_stream
     out = torch.zeros(16, dtype=torch.float32, device="cuda")
     res = {}
     for dt, iters in (("bf16", 4000), ("f32", 2000)):
-        asp.asp_probe_mfma(dt, 200, out.data_ptr(), stream)
+        measure.asp_probe_mfma(dt, 200, out.data_ptr(), stream)
         torch.cuda.synchronize()
         best = 0.0
         for _ in range(3):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            flop = asp.asp_probe_mfma(dt, iters, out.data_ptr(), stream)
+            flop = measure.asp_probe_mfma(dt, iters, out.data_ptr(), stream)
             e1.record()
             torch.cuda.synchronize()
             best = max(best, flop / (e0.elapsed_time(e1) * 1e-3) / 1e12)
@@ -308,7 +338,7 @@ def box_peaks(torch, asp):
     x = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
     y = torch.empty_like(x)
     for name, fn, nbytes in (("copy_GBs", lambda: y.copy_(x), 2 * x.numel() * 4), ("fill_GBs", lambda: y.fill_(1.0), x.numel() * 4),
-                             ("read_GBs", lambda: asp.asp_probe_read(x.data_ptr(), x.numel() * 4, out.data_ptr(), stream), x.numel() * 4)):
+                             ("read_GBs", lambda: measure.asp_probe_read(x.data_ptr(), x.numel() * 4, out.data_ptr(), stream), x.numel() * 4)):
         fn()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -370,7 +400,10 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="bcsr_gate_proj")
-    ap.add_argument("--also", default="wcsr_zipf,bcsr_gate_proj_b64,bcsr_gate_proj_f32,wcsr_zipf_bf16,bcsr_gate_proj_xt", help="comma list of further workloads reported under 'also' ('' = none)")
+    ap.add_argument("--also", default="wcsr_zipf,bcsr_gate_proj_b64,bcsr_gate_proj_f32,wcsr_zipf_bf16,bcsr_gate_proj_xt,"
+                                      "bcsr_down_proj,bcsr_down_proj_n1024_xt,bcsr_down_proj_n4096_xt,"
+                                      "wcsr_band_dense_rows,wcsr_band_dense_rows_n256,bcsr_sweep_b128_s90",
+                    help="comma list of further workloads reported under 'also' ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-reference", action="store_true",
                     help="only run a plain 1 GiB device copy (3 launches): the kernel of known size against "
@@ -428,9 +461,9 @@ def main():
     main_res = run_workload(args.workload, args.steps, args.warmup, torch, asp, synth, not args.no_cpu_baseline)
     also = []
     for name in [s for s in args.also.split(",") if s and s != args.workload]:
-        also.append(run_workload(name, args.steps, args.warmup, torch, asp, synth, not args.no_cpu_baseline))
+        also.append(run_workload(name, args.steps, args.warmup, torch, asp, synth, not args.no_cpu_baseline, cpu_seconds=4.0))
 
-    box = box_peaks(torch, asp)
+    box = box_peaks(torch)
     for r in [main_res] + also:
         roof = r["roofline"]
         if roof["bound"] == "mfma":
@@ -438,8 +471,11 @@ def main():
         else:   # the gather is nine tenths reads: against the read-only stream
             roof["frac_of_box"] = roof["achieved"] / box["read_GBs"]
     line = {
-        "metric": "effective SpMM GFLOP/s (2*nnz*N/t), BCSR gate_proj 18944x3584 bf16 128x128 blocks 90% sparse, N=16384"
-                  if args.workload == "bcsr_gate_proj" else "effective SpMM GFLOP/s (2*nnz*N/t)",
+        # (`warmup` echoes the request; the untimed warm-up runs that many calls AND at least warmup_min_ms, the
+        # number of calls it ran is warmup_calls_run)
+        "metric": ("effective SpMM GFLOP/s (2*nnz*N/t), BCSR gate_proj 18944x3584 bf16 128x128 blocks 90% sparse, N=16384"
+                   if args.workload == "bcsr_gate_proj" else "effective SpMM GFLOP/s (2*nnz*N/t)") +
+                  "; untimed warm-up = max(warmup calls, %g ms): %d calls ran" % (args.warmup_min_ms, main_res["warmup_calls_run"]),
         "value": main_res["value"], "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "warmup_min_ms": args.warmup_min_ms, "warmup_calls_run": main_res["warmup_calls_run"],
         "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,

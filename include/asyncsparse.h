@@ -60,7 +60,7 @@ typedef struct {
     int32_t dtype;     /* asp_dtype_t; both dtypes are built for both formats */
     int32_t b_row;     /* BCSR: block height in {32,64,128}; WCSR: window height in {16,32,64} */
     int32_t b_col;     /* BCSR: block width, = b_row; WCSR: column padding unit, = 8 */
-    int32_t task_cols; /* WCSR: packed columns per sub-task, positive multiple of b_col; 0 = default (512) */
+    int32_t task_cols; /* WCSR: packed columns per sub-task, positive multiple of b_col up to 2^30; 0 = default (512) */
     uint32_t flags;    /* ASP_FLAG_* */
 } asp_config_t;
 
@@ -230,24 +230,8 @@ asp_status_t asp_mtx_get(const asp_mtx_t *mx, int64_t *m, int64_t *k, int64_t *n
                          const int32_t **col_idx, const float **values);
 asp_status_t asp_mtx_free(asp_mtx_t *mx);
 
-/*
- * Measurement support: enqueue a kernel that does nothing but matrix-core instructions of the given dtype
- * (v_mfma_f32_32x32x16_bf16 or v_mfma_f32_32x32x2_f32, register operands, two waves per SIMD on every compute
- * unit) for `iters` rounds of 8 per wave, and report in *flop (HOST) how many floating-point operations that is.
- * Timed by the caller around the launch, it gives the matrix-core rate this machine sustains, beside the published
- * peak.  out_device: DEVICE, at least 4 bytes, never written in practice.  Asynchronous, allocates nothing.
- */
-asp_status_t asp_probe_mfma(int32_t dtype, int64_t iters, void *out_device, void *stream, double *flop);
-
-/*
- * Measurement support: enqueue a kernel that only reads `bytes` (rounded down to 16) of DEVICE memory at
- * src_device (16-byte aligned) with 16-byte loads -- the read-only stream that a gather-bound kernel is compared
- * with.  out_device: DEVICE, at least 4 bytes.  Asynchronous, allocates nothing.
- */
-asp_status_t asp_probe_read(const void *src_device, int64_t bytes, void *out_device, void *stream);
-
-/* host only */
-const char *asp_status_string(asp_status_t s);
+/* host only; any value is accepted (the name of an asp_status_t, "ASP_ERR_UNKNOWN" for everything else) */
+const char *asp_status_string(int status);
 const char *asp_last_error(void);
 
 #ifdef __cplusplus

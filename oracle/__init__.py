@@ -26,11 +26,24 @@ _DT = {"bf16": 0, "f32": 1}
 _NP = {"bf16": np.uint16, "f32": np.float32}
 
 
+# ASP_ORACLE_SANITIZE=1: the same source under AddressSanitizer + UndefinedBehaviorSanitizer (clang, so that its
+# runtime is the one the host-sanitized build of the library uses); the process must preload that runtime
+_SANITIZE = os.environ.get("ASP_ORACLE_SANITIZE") == "1"
+if _SANITIZE:
+    _LIB = os.path.join(_HERE, "libasp_oracle_hostsan.so")
+_CLANG = "/opt/rocm/lib/llvm/bin/clang"
+
+
 def build(force: bool = False) -> str:
     """Compile asp_oracle.c with gcc (OpenMP) into oracle/libasp_oracle.so."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra",
-                               "-o", _LIB, _SRC, "-lm"])
+        if _SANITIZE:
+            subprocess.check_call([_CLANG, "-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+                                   "-fno-sanitize-recover=undefined", "-shared-libsan", "-fopenmp", "-shared", "-fPIC",
+                                   "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"])
+        else:
+            subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra",
+                                   "-o", _LIB, _SRC, "-lm"])
     return _LIB
 
 

@@ -302,6 +302,10 @@ int64_t oracle_choose_bn(int64_t N, const int64_t *candidates, int n_candidates)
  * Tile width by cost (Section IV-C: a wider tile does more work per loaded A tile, a tile that does not divide N
  * computes on padding): the candidate with the smallest  padded_width(N, BN) x cost_per_column(BN); ties: the
  * larger.  With equal costs this is oracle_choose_bn.
+ * PARITY UNPINNED against the paper: this is not the rule Section IV-C states (that one is oracle_choose_bn, which
+ * stays pinned to the paper's printed numbers) but the rule of the library under test, written out a second
+ * time.  It is pinned only where the mathematics fixes it: equal costs reduce it to oracle_choose_bn, a widest
+ * candidate that divides N wins under any non-increasing cost table, and hand arithmetic in the tests.
  */
 int64_t oracle_choose_bn_weighted(int64_t N, const int64_t *candidates, const int64_t *cost, int n_candidates)
 {

@@ -12,7 +12,8 @@ import os
 import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libasyncsparse.so")
+# ASP_LIBRARY names another build of the same library (the host-sanitized one of the CPU-only tests)
+LIB_PATH = os.environ.get("ASP_LIBRARY") or os.path.join(_PKG, "libasyncsparse.so")
 
 ASP_OK = 0
 ASP_ERR_INVALID_ARG, ASP_ERR_INVALID_CSR, ASP_ERR_UNSUPPORTED = 1, 2, 3
@@ -29,7 +30,7 @@ _NP = {ASP_DT_BF16: np.uint16, ASP_DT_F32: np.float32}
 
 EXPORTED_SYMBOLS = [
     "asp_create_from_csr", "asp_spmm", "asp_spmm_static_scratch", "asp_spmm_xt", "asp_reserve", "asp_rcm", "asp_permute_csr",
-    "asp_mtx_read", "asp_mtx_get", "asp_mtx_free", "asp_probe_mfma", "asp_probe_read", "asp_get_info", "asp_plan_spmm", "asp_export", "asp_destroy",
+    "asp_mtx_read", "asp_mtx_get", "asp_mtx_free", "asp_get_info", "asp_plan_spmm", "asp_export", "asp_destroy",
     "asp_status_string", "asp_last_error",
 ]
 
@@ -95,10 +96,6 @@ def lib() -> ctypes.CDLL:
     L.asp_mtx_get.restype = ctypes.c_int
     L.asp_mtx_free.argtypes = [vp]
     L.asp_mtx_free.restype = ctypes.c_int
-    L.asp_probe_mfma.argtypes = [ctypes.c_int32, i64, vp, vp, ctypes.POINTER(ctypes.c_double)]
-    L.asp_probe_mfma.restype = ctypes.c_int
-    L.asp_probe_read.argtypes = [vp, i64, vp, vp]
-    L.asp_probe_read.restype = ctypes.c_int
     L.asp_get_info.argtypes = [vp, ctypes.POINTER(asp_info_t)]
     L.asp_get_info.restype = ctypes.c_int
     L.asp_plan_spmm.argtypes = [vp, i64, ctypes.POINTER(asp_plan_t)]
@@ -163,23 +160,6 @@ def asp_reserve(handle, N, check=True):
     st = lib().asp_reserve(handle, N)
     if check and st != ASP_OK:
         raise AspError(st, "asp_reserve")
-    return st
-
-
-def asp_probe_mfma(dtype, iters, out_ptr, stream=None) -> float:
-    """Enqueue the matrix-core-only kernel; returns the number of floating-point operations it performs."""
-    flop = ctypes.c_double()
-    st = lib().asp_probe_mfma(_DT.get(dtype, dtype), iters, out_ptr, stream, ctypes.byref(flop))
-    if st != ASP_OK:
-        raise AspError(st, "asp_probe_mfma")
-    return flop.value
-
-
-def asp_probe_read(src_ptr, nbytes, out_ptr, stream=None):
-    """Enqueue the read-only stream kernel over nbytes of device memory."""
-    st = lib().asp_probe_read(src_ptr, nbytes, out_ptr, stream)
-    if st != ASP_OK:
-        raise AspError(st, "asp_probe_read")
     return st
 
 

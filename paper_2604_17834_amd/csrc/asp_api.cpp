@@ -180,6 +180,8 @@ asp_status_t asp_create_from_csr(const asp_config_t *cfg, int64_t m, int64_t k, 
             return fail(ASP_ERR_UNSUPPORTED, "WCSR needs b_row in {16,32,64} and b_col = 8");
         if (cfg->task_cols < 0 || cfg->task_cols % cfg->b_col != 0)
             return fail(ASP_ERR_INVALID_ARG, "task_cols must be 0 or a positive multiple of b_col");
+        // (a window never has 2^31 packed columns; the bound keeps position + task_cols inside int32)
+        if (cfg->task_cols > (1 << 30)) return fail(ASP_ERR_INVALID_ARG, "task_cols must not exceed 2^30");
     } else {
         return fail(ASP_ERR_INVALID_ARG, "unknown format");
     }
@@ -284,19 +286,6 @@ asp_status_t asp_spmm_xt(const asp_handle_t *h, const void *X, void *Y, int64_t 
     return bcsr_spmm_xt_launch(h, X, Y, N, (hipStream_t)stream);
 }
 
-asp_status_t asp_probe_mfma(int32_t dtype, int64_t iters, void *out_device, void *stream, double *flop) {
-    if (!out_device || !flop) return fail(ASP_ERR_INVALID_ARG, "null out_device or flop");
-    if (dtype != ASP_DT_BF16 && dtype != ASP_DT_F32) return fail(ASP_ERR_INVALID_ARG, "unknown dtype");
-    if (iters < 1 || iters > (1 << 24)) return fail(ASP_ERR_INVALID_ARG, "iters out of range");
-    return probe_mfma_launch(dtype, iters, out_device, (hipStream_t)stream, flop);
-}
-
-asp_status_t asp_probe_read(const void *src_device, int64_t bytes, void *out_device, void *stream) {
-    if (!src_device || !out_device) return fail(ASP_ERR_INVALID_ARG, "null src_device or out_device");
-    if (bytes < 16 || ((uintptr_t)src_device & 15)) return fail(ASP_ERR_INVALID_ARG, "need at least 16 bytes, 16-byte aligned");
-    return probe_read_launch(src_device, bytes, out_device, (hipStream_t)stream);
-}
-
 asp_status_t asp_get_info(const asp_handle_t *h, asp_info_t *info) {
     if (!h || !info) return fail(ASP_ERR_INVALID_ARG, "null handle or info");
     info->m = h->m;
@@ -394,8 +383,8 @@ asp_status_t asp_destroy(asp_handle_t *h) {
     return ASP_OK;
 }
 
-const char *asp_status_string(asp_status_t s) {
-    switch (s) {
+const char *asp_status_string(int status) {
+    switch (status) {
         case ASP_OK: return "ASP_OK";
         case ASP_ERR_INVALID_ARG: return "ASP_ERR_INVALID_ARG";
         case ASP_ERR_INVALID_CSR: return "ASP_ERR_INVALID_CSR";

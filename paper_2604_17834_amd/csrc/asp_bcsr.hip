@@ -365,79 +365,4 @@ asp_status_t bcsr_spmm_launch(const asp_handle *h, const void *B, void *C, int64
     return ASP_OK;
 }
 
-// ---- measurement support: the matrix-core rate this machine sustains ------------------------------------
-// A loop of nothing but MFMAs on register operands, 8 independent accumulators per wave, two waves per SIMD:
-// the ceiling that the roofline fraction of the product kernels can also be read against (published peaks
-// assume the maximum clock; a box under its power limit runs slower).
-template <bool BF16>
-__global__ __launch_bounds__(256) void mfma_probe_kernel(int iters, float *__restrict__ out) {
-    const int lane = threadIdx.x & 63;
-    f32x16 acc[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
-    const float x = 1.0f + (float)(lane & 3), y = 0.5f;
-    bf16x8 a, b;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        a[e] = (__bf16)x;
-        b[e] = (__bf16)y;
-    }
-    for (int i = 0; i < iters; ++i) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            if (BF16) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
-            else acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(x, y, acc[j], 0, 0, 0);
-        }
-    }
-    float s = 0.f;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) s += acc[j][0] + acc[j][15];
-    if (s == -1.f) out[0] = s;  // never true: keeps the loop alive
-}
-
-// read-only stream over `bytes` of device memory: 16-byte loads, 8 in flight per lane, every wave on a contiguous span
-__global__ __launch_bounds__(256) void read_probe_kernel(const uint4 *__restrict__ src, int64_t n16, uint32_t *__restrict__ out) {
-    uint32_t acc = 0;
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    for (; i + 7 * stride < n16; i += 8 * stride) {
-        uint4 v[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = src[i + u * stride];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
-    }
-    for (; i < n16; i += stride) {
-        uint4 v = src[i];
-        acc ^= v.x ^ v.y ^ v.z ^ v.w;
-    }
-    if (acc == 0x9E3779B9u) out[0] = acc;  // practically never: keeps the loads alive
-}
-
-asp_status_t probe_read_launch(const void *src, int64_t bytes, void *out, hipStream_t stream) {
-    int dev = 0, cus = 0;
-    ASP_HIP_TRY(hipGetDevice(&dev));
-    ASP_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-    hipLaunchKernelGGL(read_probe_kernel, dim3(8u * (unsigned)cus), dim3(256), 0, stream, (const uint4 *)src, bytes / 16,
-                       (uint32_t *)out);
-    ASP_HIP_TRY(hipGetLastError());
-    return ASP_OK;
-}
-
-asp_status_t probe_mfma_launch(int32_t dtype, int64_t iters, void *out, hipStream_t stream, double *flop) {
-    int dev = 0, cus = 0;
-    ASP_HIP_TRY(hipGetDevice(&dev));
-    ASP_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-    const unsigned wgs = 2u * (unsigned)cus;
-    if (dtype == ASP_DT_BF16)
-        hipLaunchKernelGGL(mfma_probe_kernel<true>, dim3(wgs), dim3(256), 0, stream, (int)iters, (float *)out);
-    else
-        hipLaunchKernelGGL(mfma_probe_kernel<false>, dim3(wgs), dim3(256), 0, stream, (int)iters, (float *)out);
-    ASP_HIP_TRY(hipGetLastError());
-    *flop = (double)wgs * 4.0 * (double)iters * 8.0 * (dtype == ASP_DT_BF16 ? 2.0 * 32 * 32 * 16 : 2.0 * 32 * 32 * 2);
-    return ASP_OK;
-}
-
 }  // namespace asp

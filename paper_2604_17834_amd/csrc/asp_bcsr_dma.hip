@@ -41,22 +41,6 @@
 
 namespace asp {
 
-#ifdef ASP_TRACE
-// Debug builds only: cycle stamps of one wave (workgroup ASP_TRACE_WG, thread 0) are collected in LDS
-// (so that stamping does not touch the vector-memory counter) and copied out when the workgroup ends;
-// asp_debug_read_trace() reads them back.  Event = (tag << 56) | cycle counter.
-#define ASP_TRACE_CAP 480
-__device__ unsigned long long g_trace[ASP_TRACE_CAP];
-__device__ unsigned int g_trace_n;
-#define ASP_STAMP(tag)                                                                             \
-    do {                                                                                           \
-        if (blockIdx.x == ASP_TRACE_WG && threadIdx.x == 0 && trace_n < ASP_TRACE_CAP)             \
-            s_trace[trace_n++] = ((unsigned long long)(tag) << 56) | (__builtin_readcyclecounter() & 0xffffffffffffffull); \
-    } while (0)
-#else
-#define ASP_STAMP(tag) do {} while (0)
-#endif
-
 template <int BR, int BN, int WM, int WN, int NS>
 struct DmaCfg {
     static constexpr int KS = 32;
@@ -100,10 +84,6 @@ __global__ __launch_bounds__(WM *WN * 64, (BR / WM) * (BN / WN) > 8192 ? 1 : 2) 
     using Cfg = DmaCfg<BR, BN, WM, WN, NS>;
     constexpr int NW = Cfg::NW, KS = Cfg::KS, MT = Cfg::MT, NTL = Cfg::NTL, LPW = Cfg::LPW;
     __shared__ __attribute__((aligned(1024))) uint8_t lds[Cfg::LDS_BYTES];
-#ifdef ASP_TRACE
-    __shared__ unsigned long long s_trace[ASP_TRACE_CAP];
-    unsigned int trace_n = 0;
-#endif
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -319,18 +299,14 @@ __global__ __launch_bounds__(WM *WN * 64, (BR / WM) * (BN / WN) > 8192 ? 1 : 2) 
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-        ASP_STAMP(1);
         for (int t = 0; t < tc.T; ++t) {
-            ASP_STAMP(2);
             // Steady state: the NS-1 slices t .. t+NS-2 are in flight or landed, no store sits between them
             // (the previous tile's stores are older than slice NS-1), and the cursor is inside this tile at
             // slice t+NS-1.  Then the wait is a constant and the request code is straight-line.
             const bool steady = k_aligned && t >= NS - 1 && t + NS - 1 < tc.T && inflight == NS - 1 && !pf_in_next;
             if (steady) wait_vmcnt_and_lds<(NS - 2) * LPW>();
             else wait_outstanding(issued - mark_of(buf_c));  // this wave's part of the slice in buf_c has landed
-            ASP_STAMP(3);
             barrier_no_fence();  // everybody's part has landed; the buffer behind buf_c is free
-            ASP_STAMP(4);
             Frags f0, f1;
             load_frags(buf_c, 0, f0);  // LDS reads first: their latency runs under the request code below
             if (steady) {
@@ -362,11 +338,9 @@ __global__ __launch_bounds__(WM *WN * 64, (BR / WM) * (BN / WN) > 8192 ? 1 : 2) 
                 }
                 --inflight;
             }
-            ASP_STAMP(5);
             load_frags(buf_c, 1, f1);
             multiply(acc, f0);
             multiply(acc, f1);
-            ASP_STAMP(6);
             buf_c = buf_c + 1 == NS ? 0 : buf_c + 1;
         }
 
@@ -380,10 +354,8 @@ __global__ __launch_bounds__(WM *WN * 64, (BR / WM) * (BN / WN) > 8192 ? 1 : 2) 
         if (idx_nn < run_end) decode(idx_nn, tnn, voff_nn);
 
         // the buffer behind buf_c holds nothing that is still needed once every wave got here
-        ASP_STAMP(7);
         wait_vmcnt_and_lds<63>();
         barrier_no_fence();
-        ASP_STAMP(8);
         const bool interior = tc.br * BR + BR <= M && tc.n0 + BN <= N;
         int sbuf = buf_c == 0 ? NS - 1 : buf_c - 1;
         uint8_t *sc = lds + sbuf * Cfg::STAGE + wave * Cfg::C_WAVE;
@@ -429,14 +401,7 @@ __global__ __launch_bounds__(WM *WN * 64, (BR / WM) * (BN / WN) > 8192 ? 1 : 2) 
             mark0 = mark1 = mark2 = issued;
         }
 
-        ASP_STAMP(9);
         // ---- advance to the next tile ---------------------------------------------------------------
-#ifdef ASP_TRACE
-        if (!have_next && blockIdx.x == ASP_TRACE_WG && threadIdx.x == 0) {
-            for (unsigned int i = 0; i < trace_n; ++i) g_trace[i] = s_trace[i];
-            g_trace_n = trace_n;
-        }
-#endif
         if (!have_next) break;
         ++round;
         idx_cur = tile_of_round(round);
@@ -538,17 +503,5 @@ bool bcsr_dma_launch(const asp_handle *h, const void *B, void *C, int64_t N, con
     return false;
 }
 
-#ifdef ASP_TRACE
-extern "C" int asp_debug_read_trace(unsigned long long *dst, unsigned int cap) {
-    unsigned int n = 0;
-    if (hipMemcpyFromSymbol(&n, HIP_SYMBOL(g_trace_n), sizeof(n)) != hipSuccess) return -1;
-    if (n > cap) n = cap;
-    if (n > ASP_TRACE_CAP) n = ASP_TRACE_CAP;
-    if (hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_trace), (size_t)n * 8) != hipSuccess) return -1;
-    unsigned int zero = 0;
-    (void)hipMemcpyToSymbol(HIP_SYMBOL(g_trace_n), &zero, sizeof(zero));
-    return (int)n;
-}
-#endif
 
 }  // namespace asp

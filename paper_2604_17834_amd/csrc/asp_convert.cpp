@@ -8,6 +8,9 @@
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
+#include <exception>
+#include <mutex>
+#include <system_error>
 #include <thread>
 
 #include "asp_internal.h"
@@ -28,21 +31,34 @@ template <class F>
 void parallel_chunks(int64_t n, int64_t chunk, F fn) {
     unsigned nw = worker_count(n);
     std::atomic<int64_t> next{0};
+    // An exception inside a worker (an allocation that fails) must not leave its thread: the first one is kept,
+    // the other workers stop claiming chunks, and it is thrown again on the calling thread after all have joined.
+    std::exception_ptr first_error;
+    std::mutex error_mu;
     auto body = [&](unsigned wi) {
-        for (;;) {
-            int64_t b = next.fetch_add(chunk);
-            if (b >= n) break;
-            fn(wi, b, std::min(n, b + chunk));
+        try {
+            for (;;) {
+                int64_t b = next.fetch_add(chunk);
+                if (b >= n) break;
+                fn(wi, b, std::min(n, b + chunk));
+            }
+        } catch (...) {
+            std::lock_guard<std::mutex> lock(error_mu);
+            if (!first_error) first_error = std::current_exception();
+            next.store(n);
         }
     };
-    if (nw == 1) {
-        body(0);
-        return;
-    }
     std::vector<std::thread> th;
-    for (unsigned w = 1; w < nw; ++w) th.emplace_back(body, w);
+    for (unsigned w = 1; w < nw; ++w) {
+        try {
+            th.emplace_back(body, w);
+        } catch (const std::system_error &) {
+            break;  // no further thread to be had: the ones that run (at least the caller) do all the chunks
+        }
+    }
     body(0);
     for (auto &t : th) t.join();
+    if (first_error) std::rethrow_exception(first_error);
 }
 
 }  // namespace

@@ -154,8 +154,6 @@ inline bool bcsr_wide_capable(const asp_handle *h) { return h->has_comp || (h->b
 bool bcsr_dma_launch(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream);
 bool bcsr_f32_launch(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream);
 bool bcsr_wide_launch(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream);
-asp_status_t probe_read_launch(const void *src, int64_t bytes, void *out, hipStream_t stream);
-asp_status_t probe_mfma_launch(int32_t dtype, int64_t iters, void *out, hipStream_t stream, double *flop);
 asp_status_t bcsr_spmm_launch(const asp_handle *h, const void *B, void *C, int64_t N, hipStream_t stream);
 asp_status_t bcsr_spmm_xt_launch(const asp_handle *h, const void *X, void *Y, int64_t N, hipStream_t stream);
 

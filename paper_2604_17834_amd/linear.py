@@ -18,11 +18,15 @@ class SparseLinear:
                                               values)
 
     def __call__(self, x, out, stream=None):
-        """x: [N, in_features], out: [N, out_features], contiguous 2-byte device tensors; out is overwritten."""
+        """x: [N, in_features], out: [N, out_features], contiguous 2-byte device tensors; out is overwritten.
+        stream: a hipStream_t value; None = torch's current stream on x's device."""
         if x.shape[1] != self.in_features or out.shape != (x.shape[0], self.out_features):
             raise ValueError("shape mismatch: x %s, out %s" % (tuple(x.shape), tuple(out.shape)))
         if x.element_size() != 2 or out.element_size() != 2 or not x.is_contiguous() or not out.is_contiguous():
             raise ValueError("x and out must be contiguous bf16 (2-byte) tensors")
+        if stream is None:   # the stream that x was (or is being) produced on, not the NULL stream
+            import torch
+            stream = torch.cuda.current_stream(x.device).cuda_stream
         asp.asp_spmm_xt(self.handle, x.data_ptr(), out.data_ptr(), x.shape[0], stream)
         return out
 

@@ -233,6 +233,14 @@ def scrambled_band(m: int, seed: int, half_band: int = 13, dtype: str = F32) -> 
 # --------------------------------------------------------------------------
 # named workloads (BASELINE configs).  `scale` < 1 shrinks them for tests.
 # --------------------------------------------------------------------------
+def workload_width(name: str) -> int:
+    """Dense width N of a named workload without building its matrix ("_n<width>" overrides the default)."""
+    mm = re.search(r"_n(\d+)(?:_|$)", name)
+    if mm:
+        return int(mm.group(1))
+    raise KeyError(name)
+
+
 def workload(name: str, scale: float = 1.0):
     """Return (csr, format, b_row, b_col, N, dtype, seedB) for a named workload.
 

@@ -24,6 +24,16 @@ def test_library_exports_every_declared_symbol():
         assert getattr(L, name) is not None
 
 
+def test_measurement_library_exports_its_header_and_nothing_of_it_is_in_the_product_abi():
+    from paper_2604_17834_amd import measure
+    header = open(os.path.join(ROOT, "include", "asyncsparse_measure.h")).read()
+    declared = set(re.findall(r"\b(asp_[a-z_]+)\s*\(", header))
+    assert declared == set(measure.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert getattr(measure.lib(), name) is not None
+        assert not hasattr(asp.lib(), name)
+
+
 def test_status_strings():
     assert asp.asp_status_string(0) == "ASP_OK"
     assert asp.asp_status_string(2) == "ASP_ERR_INVALID_CSR"
@@ -50,6 +60,8 @@ def test_argument_and_csr_errors():
     assert _create_status("bcsr", 5, 64, 64, 2, 2, rp, ci, f32) == asp.ASP_ERR_INVALID_ARG     # unknown dtype
     assert _create_status("wcsr", "f32", 16, 4, 2, 2, rp, ci, f32) == asp.ASP_ERR_UNSUPPORTED
     assert _create_status("wcsr", "f32", 16, 8, 2, 2, rp, ci, f32, task_cols=12) == asp.ASP_ERR_INVALID_ARG
+    assert _create_status("wcsr", "f32", 16, 8, 2, 2, rp, ci, f32, task_cols=(1 << 30) + 8) == asp.ASP_ERR_INVALID_ARG
+    assert _create_status("wcsr", "f32", 16, 8, 2, 2, rp, ci, f32, task_cols=1 << 30) == asp.ASP_OK
     assert _create_status(7, "f32", 16, 8, 2, 2, rp, ci, f32) == asp.ASP_ERR_INVALID_ARG
     assert _create_status("wcsr", "f32", 16, 8, 0, 2, rp, ci, f32) == asp.ASP_ERR_INVALID_ARG
     assert _create_status("wcsr", "f32", 16, 8, 2, 2, rp, ci, f32, flags=HOST | 8) == asp.ASP_ERR_INVALID_ARG
@@ -224,6 +236,36 @@ def test_plan_follows_tile_width_rule():
         for N, cands in ((16384, [64, 128, 256, 512]), (8192, [64, 128, 256, 512]), (4096, [64, 128, 256]), (8192 + 64, [64, 128, 256, 512]), (16448, [64, 128, 256, 512]), (1104, [64, 128, 256])):
             p = asp.asp_plan_spmm(h, N)
             assert p.bn == oracle.choose_bn_weighted(N, cands, COST[:len(cands)]), (N, p.bn)
+    finally:
+        asp.asp_destroy(h)
+
+
+def test_tile_width_costs_are_the_measured_time_ratios_and_the_rule_meets_the_papers_where_it_must():
+    # the cost table the library ships (per column of a 64 / 128 / 256 / 512-wide tile, in 1/64 of the 512-wide
+    # tile's) must be the ratios of the kernel times of the committed tile-width study (Section IV-C's experiment on
+    # the projection workload), so that a re-measurement cannot leave the rule behind
+    text = open(os.path.join(ROOT, "profiles", "bcsr_gate_proj_ablation.txt")).read()
+    def kernel_ms(label):
+        m = re.search(r"^" + re.escape(label) + r"\s+([0-9.]+)\s+[0-9.]+\s+(\d+)\s*$", text, re.M)
+        assert m, label
+        return float(m.group(1)), int(m.group(2))
+    t512, bn512 = kernel_ms("+ 128x128 wave tiles, one wave per SIMD, hand-ordered issue, 128x512 tiles (default)")
+    t256, bn256 = kernel_ms("+ direct-to-LDS ring, resident workgroups (2 per CU), static XCD-aware schedule, 128x256 tiles")
+    t128, bn128 = kernel_ms("  same, 128x128 tiles")
+    t64, bn64 = kernel_ms("  same, 128x64 tiles")
+    assert (bn64, bn128, bn256, bn512) == (64, 128, 256, 512)
+    assert [round(64 * t / t512) for t in (t64, t128, t256, t512)] == COST
+    header = open(os.path.join(ROOT, "include", "asyncsparse.h")).read()
+    assert "costs %d / %d / %d / %d" % tuple(COST) in header
+    # Section IV-C's rule ("the largest width that divides N") and the shipped one agree whenever the widest
+    # candidate divides N; the library's plan is checked against the paper's rule there
+    a = synth.block_sparse_bernoulli(2048, 256, 128, 128, 0.0, 2)
+    h = asp.asp_create_from_csr("bcsr", "bf16", 128, 128, a.m, a.k, a.row_ptr, a.col_idx, a.values, flags=HOST)
+    try:
+        for N in (8192, 16384, 65536, 512 * 33):
+            assert asp.asp_plan_spmm(h, N).bn == oracle.choose_bn(N, [64, 128, 256, 512]) == 512
+        for N in (256, 1024, 2048, 4096):     # too few 512-wide tiles for every compute unit: 256 is the widest
+            assert asp.asp_plan_spmm(h, N).bn == oracle.choose_bn(N, [64, 128, 256]) == 256
     finally:
         asp.asp_destroy(h)
 
