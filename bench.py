@@ -351,6 +351,31 @@ def box_peaks(torch):
     return res
 
 
+def run_memory_probe(torch):
+    """Read-only streams over buffers of different sizes, each read 20 times back to back: what the memory side
+    delivers when the data fits the XCDs' L2s (4 MB each), the 256 MB memory-side cache, or only HBM.  The dense
+    operand of the headline workload (117 MB) is re-read several times per launch; this says from where."""
+    from paper_2604_17834_amd import measure
+    stream = torch.cuda.current_stream().cuda_stream
+    out = torch.zeros(16, dtype=torch.float32, device="cuda")
+    rows = []
+    big = torch.ones(1 << 30, dtype=torch.float32, device="cuda")   # 4 GiB; smaller probes read a prefix
+    for mb in (16, 64, 117, 192, 384, 1024, 4096):
+        nbytes = mb << 20
+        for _ in range(3):
+            measure.asp_probe_read(big.data_ptr(), nbytes, out.data_ptr(), stream)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 20 if mb <= 1024 else 5
+        e0.record()
+        for _ in range(reps):
+            measure.asp_probe_read(big.data_ptr(), nbytes, out.data_ptr(), stream)
+        e1.record()
+        torch.cuda.synchronize()
+        rows.append({"MiB": mb, "GB/s": nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9})
+    print(json.dumps({"memory_probe": rows, "kernel": "read-only stream, 16-byte loads, 8 in flight per lane, 8 workgroups per CU"}))
+
+
 def run_mlp_chain(args, torch, synth):
     """The three projections of the case study's feed-forward block, chained without transposes through the
     K-contiguous entry: G = X Wg^T, U = X Wu^T (18944 x 3584 weights), Y = G Wd^T (3584 x 18944); activations
@@ -408,6 +433,8 @@ def main():
     ap.add_argument("--copy-reference", action="store_true",
                     help="only run a plain 1 GiB device copy (3 launches): the kernel of known size against "
                          "which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
+    ap.add_argument("--memory-probe", action="store_true",
+                    help="read-only streams over 16 MiB .. 4 GiB, repeated: the rate from L2, the memory-side cache and HBM")
     ap.add_argument("--mlp-chain", action="store_true",
                     help="time gate, up and down projections of the feed-forward block chained through asp_spmm_xt")
     ap.add_argument("--warmup-min-ms", type=float, default=60.0,
@@ -451,6 +478,9 @@ def main():
                           "launches": 3}))
         return
     asp.lib()  # raises when the HIP library has not been built
+    if args.memory_probe:
+        run_memory_probe(torch)
+        return
     if args.mlp_chain:
         run_mlp_chain(args, torch, synth)
         return
