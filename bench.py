@@ -34,14 +34,17 @@ PAPER_CONTEXT = {
 
 
 def _measured_traffic(workload):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if one exists for this workload."""
+    """(bytes per launch through L2's memory side, kernel they were counted on) from the committed rocprofv3 --pmc
+    summary, if one exists for this workload.  A counted value, not measured in this run: the kernel's name travels
+    with it, and a CPU test checks that the name still exists in the sources with these template arguments."""
     p = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(p):
         try:
-            return json.load(open(p)).get(workload, {}).get("bytes_per_launch")
+            e = json.load(open(p)).get(workload, {})
+            return e.get("bytes_per_launch"), e.get("kernel")
         except Exception:
-            return None
-    return None
+            return None, None
+    return None, None
 
 
 _DENSE_MEMO = {}
@@ -180,7 +183,9 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline, cpu_
                  "split_windows": split_windows, "algorithmic_bytes": int(bytes_alg),
                  "mfma_flops_padded": 2.0 * info.n_units * b_row * N}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = _measured_traffic(name)
+    roof["traffic"], traffic_kernel = _measured_traffic(name)
+    if traffic_kernel:
+        roof["traffic_source"] = "profiles/hbm_traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled), kernel " + traffic_kernel
     roof["kernel_ms_avg"] = kern_ms
     if per is not None:   # the second pass ran
         roof["single_launch_ms_median"] = float(np.median(per))

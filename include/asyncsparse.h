@@ -95,7 +95,7 @@ typedef enum { ASP_ARR_ROW_PTR = 0, ASP_ARR_COL_IDX = 1, ASP_ARR_VALUES = 2, ASP
 /* How asp_spmm would run for a dense width N (Section IV-C: tile-width selection).  bf16 BCSR picks, among its
  * tile widths 64 / 128 / 256 / 512 (512: tiles of 128 rows -- 128x128 blocks, or 128-row stacks of smaller blocks where
  * the handle keeps them -- with at least one tile per compute unit), the one with the
- * least padded width x cost per column, costs 132 / 92 / 73 / 64 (ties: the wider); fp32 BCSR and WCSR take the
+ * least padded width x cost per column, costs 135 / 96 / 74 / 64 (ties: the wider); fp32 BCSR and WCSR take the
  * widest of their widths that divides N, else the one that pads least. */
 typedef struct {
     int32_t bn;          /* columns of B/C handled by one workgroup (BCSR) or one wave (WCSR) */

@@ -282,8 +282,8 @@ BcsrPlan bcsr_plan(const asp_handle *h, int64_t N, bool aligned) {
     p.vectorized = (aligned && N % 8 == 0) ? 1 : 0;
     static const int cand[4] = {64, 128, 256, 512};
     // time per column of a tile of that width relative to a 512-wide one, in 1/64 (measured on the 128x128-block
-    // projection workload at steady clocks: 0.531 / 0.370 / 0.292 / 0.257 ms for the same work)
-    static const int cost[4] = {132, 92, 73, 64};
+    // projection workload at steady clocks: 0.529 / 0.376 / 0.290 / 0.251 ms for the same work)
+    static const int cost[4] = {135, 96, 74, 64};
     // benchmarking switch only: ASP_BCSR_BN caps the tile width (it must be one of the built widths)
     static const int env_bn = [] {
         const char *e = std::getenv("ASP_BCSR_BN");

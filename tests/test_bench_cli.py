@@ -29,3 +29,33 @@ def test_workload_name_suffixes():
     assert fmt == "wcsr" and a.m == a.k == 4096 and a.nnz > 26 * 4096
     with pytest.raises(KeyError):
         synth.workload("no_such_workload")
+
+
+def test_committed_traffic_figures_name_kernels_that_exist():
+    # bench.py reports roofline.traffic from profiles/hbm_traffic.json, counted once with rocprofv3; the entry names
+    # the kernel it was counted on, and that kernel must still exist with that many template arguments
+    import glob
+    import json
+    import re
+    src = "\n".join(open(f).read() for f in glob.glob(os.path.join(ROOT, "paper_2604_17834_amd", "csrc", "*.hip")))
+    table = json.load(open(os.path.join(ROOT, "profiles", "hbm_traffic.json")))
+    checked = 0
+    for workload, entry in table.items():
+        if workload.startswith("_"):
+            continue
+        m = re.match(r"^asp::(\w+)(?:<(.*)>)?$", entry["kernel"])
+        assert m, entry["kernel"]
+        name, args = m.group(1), m.group(2)
+        d = re.search(r"template\s*<([^>]*)>\s*__global__[^;{]*?\bvoid\s+" + name + r"\s*\(", src)
+        if args is None:
+            assert re.search(r"__global__[^;{]*?\bvoid\s+" + name + r"\s*\(", src), name
+        else:
+            assert d, "no kernel template named " + name
+            assert len(d.group(1).split(",")) == len(args.split(",")), (entry["kernel"], d.group(1))
+        assert entry["bytes_per_launch"] == pytest.approx(entry["fetch_bytes"] + entry["write_bytes"], rel=2e-3)
+        checked += 1
+    assert checked >= 5
+    # the summaries under profiles/ name the headline kernel with its current template arguments
+    for f in glob.glob(os.path.join(ROOT, "profiles", "*.txt")):
+        for args in re.findall(r"bcsr_spmm_wide_kernel<([^>]*)>", open(f).read()):
+            assert len(args.split(",")) == 2, (f, args)

@@ -56,19 +56,19 @@ def test_golden_tile_width(golden_dir):
     # The weighted form is this build's own rule, not the paper's (Section IV-C states "largest width that divides
     # N"): it is pinned to the paper's rule where the two must agree -- equal costs, and whenever the widest
     # candidate divides N (no padding, least cost per column) -- and to hand arithmetic with the costs the library
-    # ships (132 / 92 / 73 / 64 per column of a 64 / 128 / 256 / 512-wide tile) elsewhere.
+    # ships (135 / 96 / 74 / 64 per column of a 64 / 128 / 256 / 512-wide tile) elsewhere.
     for N in (1, 8, 64, 100, 192, 200, 320, 1000, 1024, 1488, 16384, 16448):
         assert oracle.choose_bn_weighted(N, [64, 128, 256], [1, 1, 1]) == oracle.choose_bn(N, [64, 128, 256])
-    cand, cost = [64, 128, 256, 512], [132, 92, 73, 64]
+    cand, cost = [64, 128, 256, 512], [135, 96, 74, 64]
     for N in (512, 1024, 4096, 16384, 65536, 512 * 33):
         assert oracle.choose_bn_weighted(N, cand, cost) == oracle.choose_bn(N, cand) == 512
-    assert oracle.choose_bn_weighted(192, cand, cost) == 256     # 256*73 = 18688 < 256*92 = 23552 < 192*132 = 25344 < 512*64 = 32768
+    assert oracle.choose_bn_weighted(192, cand, cost) == 256     # 256*74 = 18944 < 256*96 = 24576 < 192*135 = 25920 < 512*64 = 32768
     assert oracle.choose_bn(192, cand) == 64                     # ... where the paper's rule takes the largest divisor
-    assert oracle.choose_bn_weighted(64, cand, cost) == 64       # 64*132 = 8448 < 128*92 = 11776
-    assert oracle.choose_bn_weighted(16448, cand, cost) == 512   # 16896*64 = 1081344 < 16640*73 < 16512*92 < 16448*132
-    assert oracle.choose_bn_weighted(320, cand, cost) == 512     # 512*64 = 32768 < 384*92 = 35328 < 512*73 < 320*132
-    assert oracle.choose_bn_weighted(1100, cand, cost) == 256    # 1280*73 = 93440 < 1536*64 = 98304 < 1152*92 < 1152*132
-    assert oracle.choose_bn_weighted(130, cand, cost) == 256     # 256*73 = 18688 < 256*92 = 23552 < 192*132
+    assert oracle.choose_bn_weighted(64, cand, cost) == 64       # 64*135 = 8640 < 128*96 = 12288
+    assert oracle.choose_bn_weighted(16448, cand, cost) == 512   # 16896*64 = 1081344 < 16640*74 < 16512*96 < 16448*135
+    assert oracle.choose_bn_weighted(320, cand, cost) == 512     # 512*64 = 32768 < 384*96 = 36864 < 512*74 < 320*135
+    assert oracle.choose_bn_weighted(1100, cand, cost) == 256    # 1280*74 = 94720 < 1536*64 = 98304 < 1152*96 < 1152*135
+    assert oracle.choose_bn_weighted(130, cand, cost) == 256     # 256*74 = 18944 < 256*96 = 24576 < 192*135
 
 
 # ------------------------------------------------------------------ BCSR
