@@ -268,6 +268,7 @@ ABLATION = [
      {"ASP_BCSR_KERNEL": "regstage", "ASP_BCSR_BN": "256"}),
     ("+ direct-to-LDS ring, resident workgroups (2 per CU), static XCD-aware schedule, 128x256 tiles",
      {"ASP_BCSR_BN": "256"}),
+    ("  same, tiles pulled from per-XCD atomic counters instead of the static schedule", {"ASP_BCSR_BN": "256", "ASP_BCSR_SCHEDULE": "atomic"}),
     ("  same, 128x128 tiles", {"ASP_BCSR_BN": "128"}),
     ("  same, 128x64 tiles", {"ASP_BCSR_BN": "64"}),
     ("+ 128x128 wave tiles, one wave per SIMD, hand-ordered issue, 128x512 tiles (default)", {}),

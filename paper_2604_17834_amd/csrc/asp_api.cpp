@@ -26,6 +26,7 @@ static void free_device(asp_handle *h) {
     (void)hipFree(h->d_tasks);
     (void)hipFree(h->d_zero_windows);
     (void)hipFree(h->d_rank_info);
+    (void)hipFree(h->d_sched);
     (void)hipFree(h->d_ws_slot);
     (void)hipFree(h->d_ws);
     (void)hipFree(h->d_c_rank_info);
@@ -98,6 +99,7 @@ static asp_status_t create_impl(const asp_config_t *cfg, int64_t m, int64_t k, i
         ASP_HIP_TRY(hipDeviceGetAttribute(&h->n_cus, hipDeviceAttributeMultiprocessorCount, h->device));
         bcsr_build_schedule(h->hb);
         if ((s = upload(&h->d_rank_info, h->hb.rank_info.data(), h->hb.rank_info.size() * 4, stream))) return s;
+        ASP_HIP_TRY(hipMalloc((void **)&h->d_sched, 64));
         if (h->has_comp) {
             if ((s = upload(&h->d_c_rank_info, h->hc.rank_info.data(), h->hc.rank_info.size() * 4, stream))) return s;
             if ((s = upload(&h->d_c_slice_rows, h->hc.slice_rows.data(), h->hc.slice_rows.size() * 4, stream))) return s;

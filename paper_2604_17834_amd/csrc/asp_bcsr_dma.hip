@@ -36,6 +36,7 @@
 // slabs of a group stay in that XCD's private L2 and A blocks are fetched once per group; inside a run
 // the XCD's workgroups take tiles round-robin, which deals sorted weights evenly.
 #include <cstdlib>
+#include <cstring>
 
 #include "asp_bcsr_pipe.h"
 
@@ -76,11 +77,18 @@ struct DmaCfg {
 };
 
 // rank_info[r] = {block-row, first stored block, number of stored blocks, block column of the first one} of the r-th heaviest block-row
-template <int BR, int BN, int WM, int WN, int NS>
+//
+// DYN = true (a benchmarking variant, ASP_BCSR_SCHEDULE=atomic: the dynamic tile scheduling that the paper's Sections
+// III-E/III-F try on Hopper and reject): the resident workgroups of an XCD pull the tiles of its run from an atomic counter
+// (sched[xcd], zeroed before the launch) instead of taking every stride-th one.  Thread 0 claims, the index travels
+// through LDS under the barrier the tile boundary has anyway; the claim for the tile after the next one is made at each
+// boundary, so its round trip is paid once per tile by wave 0.  Every workgroup leaves when its claim passes the end of
+// the run.  Calls under this switch share the handle's counters and must be ordered on one stream.
+template <int BR, int BN, int WM, int WN, int NS, bool DYN = false>
 __global__ __launch_bounds__(WM *WN * 64, (BR / WM) * (BN / WN) > 8192 ? 1 : 2) void bcsr_spmm_dma_kernel(
     const int4 *__restrict__ rank_info, const int32_t *__restrict__ block_col_idx,
     const uint16_t *__restrict__ a_packed, const uint16_t *__restrict__ B, uint16_t *__restrict__ C, int M, int K,
-    int N, int n_brows, int n_tiles, int group_n, XcdRuns runs) {
+    int N, int n_brows, int n_tiles, int group_n, XcdRuns runs, int *__restrict__ sched) {
     using Cfg = DmaCfg<BR, BN, WM, WN, NS>;
     constexpr int NW = Cfg::NW, KS = Cfg::KS, MT = Cfg::MT, NTL = Cfg::NTL, LPW = Cfg::LPW;
     __shared__ __attribute__((aligned(1024))) uint8_t lds[Cfg::LDS_BYTES];
@@ -97,7 +105,22 @@ __global__ __launch_bounds__(WM *WN * 64, (BR / WM) * (BN / WN) > 8192 ? 1 : 2) 
     const int run_end = __builtin_amdgcn_readfirstlane(runs.start[xcd + 1]);
     auto tile_of_round = [&](int r) { return run_begin + r * stride + wg; };
     int round = 0;
-    int idx_cur = tile_of_round(0);
+    int *s_claim = nullptr;  // two LDS words, only in the dynamic variant
+    if constexpr (DYN) {
+        __shared__ int claim_words[2];
+        s_claim = claim_words;
+    }
+    int idx_cur = tile_of_round(0), idx_n1 = tile_of_round(1);
+    if constexpr (DYN) {
+        if (tid == 0) {
+            s_claim[0] = run_begin + atomicAdd(&sched[xcd], 1);
+            s_claim[1] = run_begin + atomicAdd(&sched[xcd], 1);
+        }
+        __syncthreads();
+        idx_cur = __builtin_amdgcn_readfirstlane(s_claim[0]);
+        idx_n1 = __builtin_amdgcn_readfirstlane(s_claim[1]);
+        __syncthreads();  // s_claim[0] is written again at the first tile boundary
+    }
     if (idx_cur >= run_end) return;
 
     // ---- lane-invariant parts of the LDS read addresses ------------------------------------------
@@ -188,9 +211,9 @@ __global__ __launch_bounds__(WM *WN * 64, (BR / WM) * (BN / WN) > 8192 ? 1 : 2) 
     decode(idx_cur, cur_t, nxt_voff);
     cursor_enter(cur_t, nxt_voff);
     nxt_t = cur_t;
-    if (tile_of_round(1) < run_end) {
+    if (idx_n1 < run_end) {
         have_next = 1;
-        decode(tile_of_round(1), nxt_t, nxt_voff);
+        decode(idx_n1, nxt_t, nxt_voff);
     }
 
     // request the cursor's slice into ring buffer buf and move the cursor on
@@ -346,16 +369,23 @@ __global__ __launch_bounds__(WM *WN * 64, (BR / WM) * (BN / WN) > 8192 ? 1 : 2) 
 
         // ---- tile boundary ------------------------------------------------------------------------
         // parameters of the tile after the next one: requested now, needed after the epilogue
-        const int idx_nn = tile_of_round(round + 2);
+        int idx_nn = tile_of_round(round + 2);
         Tile tnn = tc;
         uint32_t voff_nn[Cfg::B_LPW];
 #pragma unroll
         for (int i = 0; i < Cfg::B_LPW; ++i) voff_nn[i] = 0;
-        if (idx_nn < run_end) decode(idx_nn, tnn, voff_nn);
+        if (!DYN && idx_nn < run_end) decode(idx_nn, tnn, voff_nn);
+        if constexpr (DYN) {
+            if (tid == 0) s_claim[0] = run_begin + atomicAdd(&sched[xcd], 1);  // read by all after the barrier below
+        }
 
         // the buffer behind buf_c holds nothing that is still needed once every wave got here
         wait_vmcnt_and_lds<63>();
         barrier_no_fence();
+        if constexpr (DYN) {
+            idx_nn = __builtin_amdgcn_readfirstlane(s_claim[0]);
+            if (idx_nn < run_end) decode(idx_nn, tnn, voff_nn);
+        }
         const bool interior = tc.br * BR + BR <= M && tc.n0 + BN <= N;
         int sbuf = buf_c == 0 ? NS - 1 : buf_c - 1;
         uint8_t *sc = lds + sbuf * Cfg::STAGE + wave * Cfg::C_WAVE;
@@ -461,6 +491,10 @@ XcdRuns cut_runs(const std::vector<int64_t> &pre, int64_t nbr, int n_tiles, int 
     return r;
 }
 
+__global__ void bcsr_zero_sched_kernel(int *__restrict__ sched) {
+    if (threadIdx.x < 8) sched[threadIdx.x] = 0;
+}
+
 template <int BR, int BN, int WM, int WN, int NS>
 static void launch_dma(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream) {
     // benchmarking switches only
@@ -482,9 +516,25 @@ static void launch_dma(const asp_handle *h, const void *B, void *C, int64_t N, c
     workers = std::max<int64_t>(8, workers / 8 * 8);  // the same number of workgroups on every XCD
     const XcdRuns runs = cut_runs(h->hb.sorted_weight_prefix, h->n_brows, p.n_tiles, group_n);
     dim3 grid((unsigned)workers), block(WM * WN * 64);
+    // benchmarking switch only: ASP_BCSR_SCHEDULE=atomic pulls tiles from per-XCD atomic counters (built for the
+    // 128 x 256 tiles of the ladder; everything else keeps the static schedule)
+    static const bool env_atomic = [] {
+        const char *e = std::getenv("ASP_BCSR_SCHEDULE");
+        return e && std::strcmp(e, "atomic") == 0;
+    }();
+    if constexpr (BR == 128 && BN == 256) {
+        if (env_atomic && h->d_sched) {
+            hipLaunchKernelGGL(bcsr_zero_sched_kernel, dim3(1), dim3(64), 0, stream, h->d_sched);
+            hipLaunchKernelGGL((bcsr_spmm_dma_kernel<BR, BN, WM, WN, NS, true>), grid, block, 0, stream,
+                               (const int4 *)h->d_rank_info, h->d_col_idx, (const uint16_t *)h->d_values,
+                               (const uint16_t *)B, (uint16_t *)C, (int)h->m, (int)h->k, (int)N, (int)h->n_brows,
+                               p.n_tiles, group_n, runs, h->d_sched);
+            return;
+        }
+    }
     hipLaunchKernelGGL((bcsr_spmm_dma_kernel<BR, BN, WM, WN, NS>), grid, block, 0, stream, (const int4 *)h->d_rank_info,
                        h->d_col_idx, (const uint16_t *)h->d_values, (const uint16_t *)B, (uint16_t *)C, (int)h->m,
-                       (int)h->k, (int)N, (int)h->n_brows, p.n_tiles, group_n, runs);
+                       (int)h->k, (int)N, (int)h->n_brows, p.n_tiles, group_n, runs, (int *)nullptr);
 }
 
 // needs N % 8 == 0, 8 <= N < 2^25 and 16-byte aligned B and C (the caller checked)

@@ -134,6 +134,7 @@ struct asp_handle {
     int32_t *d_zero_windows = nullptr;
     int32_t *d_rank_info = nullptr; // BCSR: [n_brows][4] = {block-row, first block, stored blocks, block column of the first one}, heaviest first
     int n_cus = 0;                  // compute units of the owning device
+    int32_t *d_sched = nullptr;     // BCSR: 8 tile counters of the dynamic-scheduling variant (a benchmarking switch)
     // WCSR: where the tasks of split windows put their partial tiles
     int32_t *d_ws_slot = nullptr;   // [n_windows] first scratch slot of a split window, -1 otherwise
     float *d_ws = nullptr;          // fp32 scratch, one [b_row][N] tile per slot (asp_reserve)
