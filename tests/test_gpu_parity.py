@@ -304,8 +304,12 @@ def test_bcsr_small_blocks_composite_equals_small_block_kernel_within_rounding(b
         Cn = gpu_spmm(a, "bcsr", b, b, np.ascontiguousarray(B[:, 1024:1280]), handle=h)
     finally:
         asp.asp_destroy(h)
+    # parity: each kernel against the oracle
     check_against_oracle(a, np.ascontiguousarray(B[:, 1024:1280]), Cn)
     check_against_oracle(a, np.ascontiguousarray(B[:, 1024:1280]), Cw[:, 1024:1280])
+    # not a parity claim, a diagnostic of the composite form: the two kernels add a row's products in different
+    # orders, so they may differ in the last bit of some outputs, but an indexing mistake that still lands inside
+    # the bound (two nearby columns swapped) would make them differ almost everywhere
     assert (Cw[:, 1024:1280] == Cn).mean() > 0.9
 
 
