@@ -15,6 +15,31 @@ asp_status_t fail(asp_status_t s, const std::string &msg) {
     return s;
 }
 
+const Switches &switches() {
+    static const Switches sw = [] {
+        auto num = [](const char *name, int dflt) {
+            const char *e = std::getenv(name);
+            return e ? std::atoi(e) : dflt;
+        };
+        auto is = [](const char *name, const char *value) {
+            const char *e = std::getenv(name);
+            return e && std::strcmp(e, value) == 0;
+        };
+        Switches s;
+        s.bcsr_bn = num("ASP_BCSR_BN", 0);
+        s.bcsr_regstage = is("ASP_BCSR_KERNEL", "regstage");
+        s.bcsr_group_n = num("ASP_BCSR_GROUP_N", 0);
+        s.bcsr_wgs_per_cu = num("ASP_BCSR_WGS_PER_CU", 0);
+        s.bcsr_xcd_aware = num("ASP_BCSR_XCD_AWARE", 1) != 0;
+        s.bcsr_atomic = is("ASP_BCSR_SCHEDULE", "atomic");
+        s.xt_generic = is("ASP_BCSR_XT", "generic");
+        s.bcsr_composite = num("ASP_BCSR_COMPOSITE", -1);
+        s.wcsr_max_bn = num("ASP_WCSR_MAX_BN", 256);
+        return s;
+    }();
+    return sw;
+}
+
 static void free_device(asp_handle *h) {
     if (h->device < 0) return;
     int cur = -1;
@@ -72,10 +97,7 @@ static asp_status_t create_impl(const asp_config_t *cfg, int64_t m, int64_t k, i
         // ASP_BCSR_COMPOSITE=0/1 is a benchmarking switch.
         // (128x128 blocks take the same form when K is not a multiple of 128: it keeps every K slice inside K)
         if (cfg->dtype == ASP_DT_BF16 && (cfg->b_row < 128 || k % 128 != 0) && k >= 32 && h->n_units > 0) {
-            static const int env_comp = [] {
-                const char *e = std::getenv("ASP_BCSR_COMPOSITE");
-                return e ? std::atoi(e) : -1;
-            }();
+            const int env_comp = switches().bcsr_composite;
             if (env_comp != 0) {
                 h->comp_inflation = bcsr_build_composite(h->hb, m, k, cfg->b_row, h->hc);
                 const double limit = cfg->b_row == 128 ? 1.0 : cfg->b_row == 64 ? 2.6 : 4.3;  // 128: no fill

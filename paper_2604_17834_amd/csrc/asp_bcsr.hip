@@ -284,11 +284,7 @@ BcsrPlan bcsr_plan(const asp_handle *h, int64_t N, bool aligned) {
     // time per column of a tile of that width relative to a 512-wide one, in 1/64 (measured on the 128x128-block
     // projection workload at steady clocks: 0.529 / 0.376 / 0.290 / 0.251 ms for the same work)
     static const int cost[4] = {135, 96, 74, 64};
-    // benchmarking switch only: ASP_BCSR_BN caps the tile width (it must be one of the built widths)
-    static const int env_bn = [] {
-        const char *e = std::getenv("ASP_BCSR_BN");
-        return e ? std::atoi(e) : 0;
-    }();
+    const int env_bn = switches().bcsr_bn;  // benchmarking switch: caps the tile width
     if (!p.vectorized) {
         p.bn = 64;  // the element-wise path is only built for BN = 64
     } else {
@@ -332,11 +328,7 @@ asp_status_t bcsr_spmm_launch(const asp_handle *h, const void *B, void *C, int64
         return ASP_OK;
     }
     const int key = h->b_row * 1000 + p.bn;
-    // benchmarking switch only: ASP_BCSR_KERNEL=regstage selects the synchronous-copy kernel
-    static const bool force_regstage = [] {
-        const char *e = std::getenv("ASP_BCSR_KERNEL");
-        return e && std::strcmp(e, "regstage") == 0;
-    }();
+    const bool force_regstage = switches().bcsr_regstage;  // benchmarking switch: the synchronous-copy kernel
     if (p.vectorized && !force_regstage && N < (1ll << 25)) {
         if (!bcsr_wide_launch(h, B, C, N, p, stream) && !bcsr_dma_launch(h, B, C, N, p, stream))
             return fail(ASP_ERR_UNSUPPORTED, "no kernel for this block size / tile width");

@@ -497,15 +497,7 @@ __global__ void bcsr_zero_sched_kernel(int *__restrict__ sched) {
 
 template <int BR, int BN, int WM, int WN, int NS>
 static void launch_dma(const asp_handle *h, const void *B, void *C, int64_t N, const BcsrPlan &p, hipStream_t stream) {
-    // benchmarking switches only
-    static const int env_group = [] {
-        const char *e = std::getenv("ASP_BCSR_GROUP_N");
-        return e ? std::atoi(e) : 0;
-    }();
-    static const int env_wgs = [] {
-        const char *e = std::getenv("ASP_BCSR_WGS_PER_CU");
-        return e ? std::atoi(e) : 0;
-    }();
+    const int env_group = switches().bcsr_group_n, env_wgs = switches().bcsr_wgs_per_cu;  // benchmarking switches
     int group_n = env_group > 0 ? env_group : 4;
     if (group_n > p.n_tiles) group_n = p.n_tiles;
     // resident workgroups per CU: as many as LDS allows (the kernel is built for 2 waves per SIMD)
@@ -516,12 +508,9 @@ static void launch_dma(const asp_handle *h, const void *B, void *C, int64_t N, c
     workers = std::max<int64_t>(8, workers / 8 * 8);  // the same number of workgroups on every XCD
     const XcdRuns runs = cut_runs(h->hb.sorted_weight_prefix, h->n_brows, p.n_tiles, group_n);
     dim3 grid((unsigned)workers), block(WM * WN * 64);
-    // benchmarking switch only: ASP_BCSR_SCHEDULE=atomic pulls tiles from per-XCD atomic counters (built for the
-    // 128 x 256 tiles of the ladder; everything else keeps the static schedule)
-    static const bool env_atomic = [] {
-        const char *e = std::getenv("ASP_BCSR_SCHEDULE");
-        return e && std::strcmp(e, "atomic") == 0;
-    }();
+    // benchmarking switch: tiles pulled from per-XCD atomic counters (built for the 128 x 256 tiles of the ladder;
+    // everything else keeps the static schedule)
+    const bool env_atomic = switches().bcsr_atomic;
     if constexpr (BR == 128 && BN == 256) {
         if (env_atomic && h->d_sched) {
             hipLaunchKernelGGL(bcsr_zero_sched_kernel, dim3(1), dim3(64), 0, stream, h->d_sched);

@@ -638,10 +638,7 @@ static WideOperand wide_operand(const asp_handle *h) {
 
 template <bool XT>
 static void launch_wide(const asp_handle *h, const void *B, void *C, int64_t N, int n_tiles, hipStream_t stream) {
-    static const int env_group = [] {  // benchmarking switch only
-        const char *e = std::getenv("ASP_BCSR_GROUP_N");
-        return e ? std::atoi(e) : 0;
-    }();
+    const int env_group = switches().bcsr_group_n;  // benchmarking switch
     // two N-tiles walked together: an A block is fetched once per pair while the pair's slab of B (K x 1024)
     // still has a chance in the 4 MB of L2 (measured: 1, 3 and 4 are 3-10 % slower on the 90 %-sparse projection)
     int group_n = env_group > 0 ? env_group : 2;
@@ -651,10 +648,7 @@ static void launch_wide(const asp_handle *h, const void *B, void *C, int64_t N, 
     int64_t workers = h->n_cus;  // one resident workgroup per CU: the ring takes the whole LDS
     if (workers > n_rows * n_tiles) workers = n_rows * n_tiles;
     workers = std::max<int64_t>(8, workers / 8 * 8);  // the same number of workgroups on every XCD
-    static const int env_xcd = [] {  // benchmarking switch only: 0 = ignore the XCDs when dealing tiles
-        const char *e = std::getenv("ASP_BCSR_XCD_AWARE");
-        return e ? std::atoi(e) : 1;
-    }();
+    const int env_xcd = switches().bcsr_xcd_aware ? 1 : 0;  // benchmarking switch: 0 = ignore the XCDs when dealing tiles
     XcdRuns runs = cut_runs(*op.weight_prefix, n_rows, n_tiles, group_n);
     if (!env_xcd)
         for (int x = 1; x <= 8; ++x) runs.start[x] = runs.start[8];
@@ -741,11 +735,7 @@ asp_status_t bcsr_spmm_xt_launch(const asp_handle *h, const void *X, void *Y, in
     } else {
         const bool aligned = (((uintptr_t)X | (uintptr_t)Y) & 15) == 0;
         const int64_t n_tiles = ceil_div(N, 512);
-        // benchmarking switch only: ASP_BCSR_XT=generic forces the fallback
-        static const bool force_generic = [] {
-            const char *e = std::getenv("ASP_BCSR_XT");
-            return e && std::strcmp(e, "generic") == 0;
-        }();
+        const bool force_generic = switches().xt_generic;  // benchmarking switch: forces the fallback
         // (no lower bound on the number of tiles: with fewer 128 x 512 tiles than compute units part of the chip
         // idles, which still is two orders of magnitude faster than the generic kernel -- the down projection of
         // the case study has 28 block-rows and would need 4600 tokens to give every compute unit a tile)

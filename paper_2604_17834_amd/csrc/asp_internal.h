@@ -25,6 +25,22 @@ asp_status_t fail(asp_status_t s, const std::string &msg);
                                std::string(#expr) + ": " + hipGetErrorString(e__));             \
     } while (0)
 
+// Benchmarking switches: environment variables that select among kernels and schedules which are all built and
+// parity-tested, for the ladder and the tile-width study of bench.py.  Read once per process, in one place
+// (asp_api.cpp); nothing else in the library looks at the environment.
+struct Switches {
+    int bcsr_bn;          // ASP_BCSR_BN=64|128|256: widest BCSR tile to consider (0: no cap)
+    bool bcsr_regstage;   // ASP_BCSR_KERNEL=regstage: the synchronous register-staged kernel
+    int bcsr_group_n;     // ASP_BCSR_GROUP_N=<n>: N-tiles walked together (0: the kernels' defaults, 2 and 4)
+    int bcsr_wgs_per_cu;  // ASP_BCSR_WGS_PER_CU=<n>: resident workgroups of the ring kernel (0: as many as LDS allows)
+    bool bcsr_xcd_aware;  // ASP_BCSR_XCD_AWARE=0: deal tiles without regard to XCDs
+    bool bcsr_atomic;     // ASP_BCSR_SCHEDULE=atomic: tiles pulled from per-XCD atomic counters (ring kernel, 128x256)
+    bool xt_generic;      // ASP_BCSR_XT=generic: asp_spmm_xt without matrix cores
+    int bcsr_composite;   // ASP_BCSR_COMPOSITE=0|1: never / always keep the 128-row stacks of smaller blocks (-1: by fill)
+    int wcsr_max_bn;      // ASP_WCSR_MAX_BN=64|128|256: widest fp32 WCSR wave tile to consider
+};
+const Switches &switches();
+
 inline size_t dtype_size(int32_t dt) { return dt == ASP_DT_BF16 ? 2 : 4; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 

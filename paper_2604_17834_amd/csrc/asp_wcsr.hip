@@ -492,10 +492,7 @@ WcsrPlan wcsr_plan(const asp_handle *h, int64_t N, bool aligned) {
     if (h->b_row == 16) {
         // Section IV-C rule over the built wave widths: widest that divides N, else least padding
         static const int cand[3] = {64, 128, 256};
-        static const int env_max = [] {  // benchmarking switch only: widest wave tile to consider
-            const char *e = std::getenv("ASP_WCSR_MAX_BN");
-            return e ? std::atoi(e) : 256;
-        }();
+        const int env_max = switches().wcsr_max_bn;  // benchmarking switch: widest wave tile to consider
         int best = -1;
         for (int c : cand)
             if (c <= env_max && N % c == 0 && c > best) best = c;

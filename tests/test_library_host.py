@@ -350,3 +350,17 @@ def test_spmm_entries_refuse_host_only_handles_and_null_pointers():
             assert fn(h, 16, 32, 0, None, check=False) == asp.ASP_ERR_INVALID_ARG
     finally:
         asp.asp_destroy(h)
+
+
+def test_every_benchmarking_switch_has_a_gpu_parity_case():
+    # the library reads its environment in exactly one place; every variable named there must be exercised by
+    # tests/test_gpu_variants.py (one child process per setting, against the oracle)
+    import glob
+    srcs = {f: open(f).read() for f in glob.glob(os.path.join(ROOT, "paper_2604_17834_amd", "csrc", "*"))}
+    readers = [f for f, text in srcs.items() if "getenv" in text]
+    assert [os.path.basename(f) for f in readers] == ["asp_api.cpp"]
+    names = set(re.findall(r'"(ASP_[A-Z_]+)"', srcs[readers[0]]))
+    assert len(names) == 9
+    cases = open(os.path.join(ROOT, "tests", "test_gpu_variants.py")).read()
+    for n in names:
+        assert '"%s"' % n in cases, n
