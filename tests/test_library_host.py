@@ -359,7 +359,7 @@ def test_every_benchmarking_switch_has_a_gpu_parity_case():
     srcs = {f: open(f).read() for f in glob.glob(os.path.join(ROOT, "paper_2604_17834_amd", "csrc", "*"))}
     readers = [f for f, text in srcs.items() if "getenv" in text]
     assert [os.path.basename(f) for f in readers] == ["asp_api.cpp"]
-    names = set(re.findall(r'"(ASP_[A-Z_]+)"', srcs[readers[0]]))
+    names = set(re.findall(r'"(ASP_(?:BCSR|WCSR)_[A-Z_]+)"', srcs[readers[0]]))
     assert len(names) == 9
     cases = open(os.path.join(ROOT, "tests", "test_gpu_variants.py")).read()
     for n in names:
