@@ -233,10 +233,16 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline, cpu_
             sl = Bd[:n].T if xt else Bd[:, :n]
             h = sl.contiguous().cpu().numpy()
             return h.view(np.uint16) if dt == "bf16" else h
-        Bp = first_columns(probe)
-        t0 = time.perf_counter()
-        oracle.spmm(a.m, a.k, a.row_ptr, a.col_idx, a.values, dt, Bp)
-        tp = time.perf_counter() - t0
+        # size the sample from probes: widen the probe until it runs for half a second (a 16-column probe is mostly
+        # fixed cost and overestimates the time per column several times), then scale to the target
+        while True:
+            Bp = first_columns(probe)
+            t0 = time.perf_counter()
+            oracle.spmm(a.m, a.k, a.row_ptr, a.col_idx, a.values, dt, Bp)
+            tp = time.perf_counter() - t0
+            if tp >= 0.5 or probe >= N:
+                break
+            probe = min(N, probe * 8)
         ncols = int(max(probe, min(N, cpu_seconds / max(tp / probe, 1e-9))))
         ncols = max(16, ncols // 16 * 16) if N >= 16 else N
         Bs = first_columns(ncols)
