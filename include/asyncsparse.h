@@ -15,7 +15,8 @@
  *   - A handle is immutable after creation: concurrent asp_spmm calls on
  *     different streams with different C buffers are safe.  The one exception
  *     is a WCSR handle whose split windows go through the handle's scratch
- *     buffer (asp_reserve): those calls must be ordered on one stream.
+ *     buffer (asp_reserve): those calls must be ordered on one stream; calls
+ *     of asp_spmm_static_scratch share one scratch array per GPU in the same way.
  *   - The library needs a gfx950 GPU for everything except the calls marked
  *     "host only".  There is no CPU fallback for the product.
  */
@@ -38,7 +39,8 @@ typedef enum {
     ASP_ERR_UNSUPPORTED = 3,      /* block/window size, dtype or mode not built */
     ASP_ERR_OUT_OF_MEMORY = 4,
     ASP_ERR_HIP = 5,              /* a HIP runtime call failed (no GPU, launch error, ...) */
-    ASP_ERR_BUFFER_TOO_SMALL = 6  /* asp_export: dst_bytes < *needed; asp_spmm: scratch not reserved for this N */
+    ASP_ERR_BUFFER_TOO_SMALL = 6  /* asp_export: dst_bytes < *needed; asp_spmm: scratch not reserved for this N;
+                                     asp_spmm_static_scratch: the static scratch is too small for this handle and N */
 } asp_status_t;
 
 typedef enum { ASP_FMT_BCSR = 0, ASP_FMT_WCSR = 1 } asp_format_t;
