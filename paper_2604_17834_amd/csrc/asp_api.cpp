@@ -204,7 +204,7 @@ asp_status_t asp_create_from_csr(const asp_config_t *cfg, int64_t m, int64_t k, 
             return fail(ASP_ERR_UNSUPPORTED, "WCSR needs b_row in {16,32,64} and b_col = 8");
         if (cfg->task_cols < 0 || cfg->task_cols % cfg->b_col != 0)
             return fail(ASP_ERR_INVALID_ARG, "task_cols must be 0 or a positive multiple of b_col");
-        // (a window never has 2^31 packed columns; the bound keeps position + task_cols inside int32)
+        // (a window never has 2^31 packed columns: a larger task size means nothing; sums with it are taken in 64 bits)
         if (cfg->task_cols > (1 << 30)) return fail(ASP_ERR_INVALID_ARG, "task_cols must not exceed 2^30");
     } else {
         return fail(ASP_ERR_INVALID_ARG, "unknown format");

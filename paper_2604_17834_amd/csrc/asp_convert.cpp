@@ -521,10 +521,10 @@ void wcsr_tasks_host(const std::vector<int32_t> &wrp, int32_t task_cols, std::ve
     for (size_t w = 0; w + 1 < wrp.size(); ++w) {
         const int32_t lo = wrp[w], hi = wrp[w + 1];
         const int32_t split = (hi - lo > task_cols) ? 1 : 0;
-        for (int32_t c = lo; c < hi; c += task_cols) {
+        for (int64_t c = lo; c < hi; c += task_cols) {  // 64-bit: position + task_cols may pass 2^31
             tasks.push_back((int32_t)w);
-            tasks.push_back(c);
-            tasks.push_back(std::min(hi, c + task_cols));
+            tasks.push_back((int32_t)c);
+            tasks.push_back((int32_t)std::min<int64_t>(hi, c + task_cols));
             tasks.push_back(split);
         }
     }

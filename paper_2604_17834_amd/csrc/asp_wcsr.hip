@@ -88,7 +88,7 @@ __global__ __launch_bounds__(256) void wcsr_sum_partials_kernel(const int32_t *_
     const int w = zero_windows[blockIdx.x];
     const int slot0 = ws_slot[w];
     if (slot0 < 0) return;  // a window without columns
-    const int parts = (window_row_ptr[w + 1] - window_row_ptr[w] + task_cols - 1) / task_cols;
+    const int parts = (int)(((int64_t)window_row_ptr[w + 1] - window_row_ptr[w] + task_cols - 1) / task_cols);
     const int64_t r0 = (int64_t)w * b_row, r1 = r0 + b_row < M ? r0 + b_row : M;
     const int64_t units = (r1 - r0) * N / U, tile = (int64_t)b_row * N / U;
     const vec_t *src = (const vec_t *)(ws + (int64_t)slot0 * b_row * N);
@@ -383,7 +383,8 @@ __global__ __launch_bounds__(256) void wcsr_task_count_kernel(const int32_t *__r
                                                               int32_t *__restrict__ block_sums) {
     const int w = blockIdx.x * 256 + threadIdx.x;
     int cnt = 0;
-    if (w < n_windows) cnt = (window_row_ptr[w + 1] - window_row_ptr[w] + task_cols - 1) / task_cols;
+    // (64-bit: width + task_cols may pass 2^31)
+    if (w < n_windows) cnt = (int)(((int64_t)window_row_ptr[w + 1] - window_row_ptr[w] + task_cols - 1) / task_cols);
     int total;
     int inc = block_inclusive_scan(cnt, &total);
     if (w < n_windows) local_excl[w] = inc - cnt;
@@ -424,12 +425,12 @@ __global__ __launch_bounds__(256) void wcsr_task_emit_kernel(const int32_t *__re
         if (task_offsets[mid] <= t) lo = mid; else hi = mid;
     }
     const int w = lo;
-    const int begin = window_row_ptr[w] + (t - task_offsets[w]) * task_cols;
-    const int wend = window_row_ptr[w + 1];
+    const int64_t begin = window_row_ptr[w] + (int64_t)(t - task_offsets[w]) * task_cols;  // 64-bit: see above
+    const int64_t wend = window_row_ptr[w + 1];
     int4 d;
     d.x = w;
-    d.y = begin;
-    d.z = begin + task_cols < wend ? begin + task_cols : wend;
+    d.y = (int)begin;
+    d.z = (int)(begin + task_cols < wend ? begin + task_cols : wend);
     d.w = (task_offsets[w + 1] - task_offsets[w]) > 1 ? 1 : 0;
     tasks[t] = d;
 }
