@@ -231,7 +231,7 @@ def scrambled_band(m: int, seed: int, half_band: int = 13, dtype: str = F32) -> 
 
 
 # --------------------------------------------------------------------------
-# named workloads (BASELINE configs).  `scale` < 1 shrinks them for tests.
+# named workloads (the five benchmark configurations and their variants).  `scale` < 1 shrinks them for tests.
 # --------------------------------------------------------------------------
 def workload_width(name: str) -> int:
     """Dense width N of a named workload without building its matrix ("_n<width>" overrides the default)."""
