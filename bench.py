@@ -185,8 +185,9 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline, cpu_
     roof["frac"] = roof["achieved"] / roof["peak"]
     if fmt == "bcsr" and dt == "bf16":
         # (counter evidence, not measured in this run: profiles/bench_default_pmc.txt)
-        roof["limiter"] = ("reads in flight per L1 (about 120 lines of 128 B per CU) x their latency; the matrix cores are "
-                           "busy 0.40 of the cycles on the 90 %-sparse projection")
+        roof["limiter"] = ("0.56 of the time is the instruction stream of one wave per SIMD (kernel without loads and stores), "
+                           "the rest memory: reads in flight per L1 (about 120 lines of 128 B per CU) x their latency, and the "
+                           "stores of C; the matrix cores are busy 0.40 of the cycles on the 90 %-sparse projection")
     roof["traffic"], traffic_kernel = _measured_traffic(name)
     if traffic_kernel:
         roof["traffic_source"] = "profiles/hbm_traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled), kernel " + traffic_kernel
