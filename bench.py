@@ -164,7 +164,9 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline, cpu_
         flops_alg = 2.0 * info.n_units * b_row * b_col * N
         bytes_alg = info.n_units * b_row * b_col * esz + a.k * N * esz + a.m * N * esz
         peak = PEAK_BF16_TFLOPS if dt == "bf16" else PEAK_F32_TFLOPS
-        roof = {"bound": "mfma", "achieved": flops_alg / (kern_ms * 1e-3) / 1e12, "peak": peak, "unit": "TFLOP/s"}
+        roof = {"bound": "mfma", "achieved": flops_alg / (kern_ms * 1e-3) / 1e12, "peak": peak, "unit": "TFLOP/s",
+                # the same launch against the other roof: compulsory bytes (A once, B once, C once) over the HBM peak
+                "frac_of_hbm_roof": bytes_alg / (kern_ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
         extra = {"stored_blocks": int(info.n_units), "algorithmic_bytes": int(bytes_alg),
                  "hbm_floor_ms": bytes_alg / (PEAK_HBM_GBS * 1e9) * 1e3,
                  "mfma_floor_ms": flops_alg / (peak * 1e12) * 1e3}
