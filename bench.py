@@ -335,6 +335,66 @@ def run_sweep(args, torch, asp, synth):
     print(json.dumps({"sweep": rows, "steps": args.steps, "warmup": args.warmup}))
 
 
+# The paper's kernel-level case study (Section IV-D, the table of gate_proj latencies): 18944 x 3584 bf16, randomly
+# block-sparsified, four sparsity levels x four sequence lengths, against the dense product of the same shape.
+# The last two numbers of a cell are what the paper prints for its kernel on its hardware (latency, speedup over the
+# dense library call there): context, not a target.
+CASE_STUDY_PAPER = {
+    (80, 1024): (0.17, 1.46), (90, 1024): (0.14, 1.58), (95, 1024): (0.12, 1.89), (99, 1024): (0.09, 2.60),
+    (80, 4096): (0.55, 1.57), (90, 4096): (0.44, 1.98), (95, 4096): (0.39, 2.18), (99, 4096): (0.28, 3.04),
+    (80, 16384): (2.06, 1.59), (90, 16384): (1.70, 1.92), (95, 16384): (1.46, 2.24), (99, 16384): (1.05, 3.19),
+    (80, 65536): (8.12, 1.67), (90, 65536): (6.69, 1.96), (95, 65536): (5.88, 2.23), (99, 65536): (4.21, 3.06),
+}
+
+
+def run_case_study_grid(args, torch, asp, synth):
+    global SINGLE_LAUNCHES
+    SINGLE_LAUNCHES = False
+    M, K = 18944, 3584
+    dense_ms = {}
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1)
+    Ad = (torch.randn((M, K), device="cuda", generator=gen) * 0.02).to(torch.bfloat16)
+    for N in (1024, 4096, 16384, 65536):
+        Bb = torch.randn((K, N), device="cuda", generator=gen).to(torch.bfloat16)
+        t_w = time.perf_counter()
+        while (time.perf_counter() - t_w) * 1e3 < WARMUP_MIN_MS:
+            torch.matmul(Ad, Bb)
+            torch.cuda.synchronize()
+        reps = 50 if N <= 16384 else 10
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            torch.matmul(Ad, Bb)
+        e1.record()
+        torch.cuda.synchronize()
+        dense_ms[N] = e0.elapsed_time(e1) / reps
+        del Bb
+    del Ad
+    torch.cuda.empty_cache()
+    rows = []
+    for blk in (128, 64):
+        for pct in (80, 90, 95, 99):
+            for N in (1024, 4096, 16384, 65536):
+                name = "bcsr_gate_proj" + ("" if pct == 90 else "_s%d" % pct) + ("" if blk == 128 else "_b%d" % blk) + \
+                       ("" if N == 16384 else "_n%d" % N)
+                steps = args.steps if N <= 16384 else max(10, args.steps // 4)
+                r = run_workload(name, steps, min(args.warmup, steps), torch, asp, synth, False)
+                ms = r["roofline"]["kernel_ms_avg"]
+                paper = CASE_STUDY_PAPER[(pct, N)]
+                rows.append({"workload": name, "block": blk, "sparsity_pct": pct, "N": N, "stored_blocks": r["stored_blocks"],
+                             "bn": r["bn"], "kernel_ms": ms, "effective_TFLOP/s": r["value"] / 1e3,
+                             "frac_of_mfma_peak": r["roofline"]["frac"], "dense_ms": dense_ms[N],
+                             "speedup_over_dense": dense_ms[N] / ms,
+                             "paper_kernel_latency": paper[0], "paper_speedup_over_dense": paper[1]})
+                print("grid", name, "%.4f ms" % ms, "dense %.4f ms" % dense_ms[N], "x%.2f" % (dense_ms[N] / ms),
+                      file=sys.stderr, flush=True)
+                torch.cuda.empty_cache()
+    print(json.dumps({"case_study_grid": rows, "dense": "torch.matmul (bf16, vendor GEMM) of 18944 x 3584 by 3584 x N",
+                      "paper_context": "Section IV-D kernel-level table, other hardware, 64 x 64 blocks",
+                      "steps": args.steps}))
+
+
 def box_peaks(torch):
     """What this machine sustains, beside the published peaks: matrix-core rate of an MFMA-only loop (both dtypes) and
     the bandwidth of a plain 1 GiB device copy (read + write), of a 1 GiB fill (write only) and of a read-only stream over 1 GiB."""
@@ -464,6 +524,9 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="the long-prefill BCSR grid (block sizes x sparsities) and the band + long rows WCSR workload at "
                          "both widths: one JSON object, no CPU baseline")
+    ap.add_argument("--case-study-grid", action="store_true",
+                    help="the paper's kernel-level case study: gate_proj at 4 sparsity levels x 4 sequence lengths, "
+                         "128- and 64-wide blocks, with the dense product beside each")
     ap.add_argument("--ablation", action="store_true",
                     help="run the BCSR workload once per kernel variant (child processes) and print one JSON object")
     args = ap.parse_args()
@@ -505,6 +568,9 @@ def main():
         return
     if args.sweep:
         run_sweep(args, torch, asp, synth)
+        return
+    if args.case_study_grid:
+        run_case_study_grid(args, torch, asp, synth)
         return
 
     main_res = run_workload(args.workload, args.steps, args.warmup, torch, asp, synth, not args.no_cpu_baseline)

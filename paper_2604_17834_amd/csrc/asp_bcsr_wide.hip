@@ -108,33 +108,62 @@ __global__ __launch_bounds__(256, 1) void bcsr_spmm_wide_kernel(
     auto tile_of_round = [&](int r) __attribute__((always_inline)) {
         return run_begin + r * stride + wg;
     };
-    // Rows of C of block-rows without stored blocks (ranks n_rows .. n_brows-1): every workgroup clears
-    // its share of each of them when its stream has ended (whole rows: one contiguous span, N % 8 == 0).
-    // (XT: the block-row's outputs are up to 256 bytes in every row of Y)
+    // Rows of C of block-rows without stored blocks (ranks n_rows .. n_brows-1; GATHER: four pieces of 32 rows per
+    // super-row, placed by piece_rows) are cleared by the workgroups when their streams have ended.  Every such
+    // span of rows is cut into `parts` equal parts and workgroup b takes the (span, part) items b, b + grid, ...:
+    // a part per workgroup when the spans are few (equal shares, as many steps as spans), else so many parts
+    // that a workgroup gets at least eight items (hundreds of small spans: a step per span and workgroup would
+    // cost more than its one store).  A lane looks up the first row of one of the workgroup's items, 64 items
+    // at a time: looked up one by one, the two dependent loads per item cost more than its stores.
+    // (XT: a span is up to 256 bytes in every row of Y, and a part is a range of tokens)
     auto clear_empty_rows = [&]() __attribute__((always_inline)) {
         const uint4 z = {0u, 0u, 0u, 0u};
-        for (int e = n_rows * (GATHER ? 4 : 1); e < n_brows * (GATHER ? 4 : 1); ++e) {
-            // GATHER: piece e % 4 of super-row e / 4, 32 rows starting at its entry of piece_rows
-            const int br = __builtin_amdgcn_readfirstlane(rank_info[GATHER ? e >> 2 : e].x);
-            int r0 = br * Cfg::BR, r1 = r0 + Cfg::BR < M ? r0 + Cfg::BR : M;
-            if (GATHER) {
-                const int4 pr = piece_rows[br];
-                r0 = __builtin_amdgcn_readfirstlane((e & 3) == 0 ? pr.x : (e & 3) == 1 ? pr.y : (e & 3) == 2 ? pr.z : pr.w);
-                if (r0 < 0 || r0 >= M) continue;
-                r1 = r0 + 32 < M ? r0 + 32 : M;
+        const int first = n_rows * (GATHER ? 4 : 1), count = n_brows * (GATHER ? 4 : 1) - first;
+        if (count <= 0) return;
+        const int grid = (int)gridDim.x, b = (int)blockIdx.x;
+        constexpr int rows_full = GATHER ? 32 : Cfg::BR;
+        // units of a part: 16 bytes (row-major C, whole rows are one contiguous span) or tokens (XT)
+        const int64_t span_full = XT ? (int64_t)N : (int64_t)rows_full * N / 8;
+        const int64_t chunks = (span_full + 63) / 64;  // a part is at least what one pass of the workgroup's waves stores
+        int parts = count >= 8 * grid ? 1 : (8 * grid + count - 1) / count;
+        if (2 * count <= grid && chunks >= grid) parts = grid;
+        if (parts > chunks) parts = (int)chunks;
+        const int items = count * parts;  // <= grid * grid / 2, < 16 * grid, or count
+        if (b >= items) return;
+        const int mine = (items - b + grid - 1) / grid;
+        // (whole kilobytes, so that no store of a wave straddles two parts' cache lines)
+        const int64_t per = XT ? (span_full + parts - 1) / parts : ((span_full + parts - 1) / parts + 63) / 64 * 64;
+        for (int base = 0; base < mine; base += 64) {
+            const int item = b + (base + lane) * grid;
+            int r0_l = -1, part_l = 0;
+            if (base + lane < mine) {
+                const int e = first + item / parts;
+                part_l = item % parts;
+                const int br = rank_info[GATHER ? e >> 2 : e].x;
+                if (GATHER) {
+                    const int4 pr = piece_rows[br];
+                    r0_l = (e & 3) == 0 ? pr.x : (e & 3) == 1 ? pr.y : (e & 3) == 2 ? pr.z : pr.w;
+                } else {
+                    r0_l = br * Cfg::BR;
+                }
             }
-            if (!XT) {
-                uint16_t *dst = C + (int64_t)r0 * N;
-                const int64_t n16 = (int64_t)(r1 - r0) * N / 8;
-                const int64_t per = (n16 + gridDim.x - 1) / gridDim.x;
-                const int64_t lo = per * blockIdx.x, hi = lo + per < n16 ? lo + per : n16;
-                for (int64_t i = lo + tid; i < hi; i += 256) store_c16(dst + i * 8, z);
-            } else {
-                const int cpr = (r1 - r0) / 8;  // 16-byte units per row (M % 8 == 0)
-                const int64_t per = ((int64_t)N + gridDim.x - 1) / gridDim.x;
-                const int64_t lo = per * blockIdx.x, hi = lo + per < N ? lo + per : N;
-                for (int64_t t = lo + (tid >> 4); t < hi; t += 16)
-                    if ((tid & 15) < cpr) store_c16(C + t * M + r0 + (tid & 15) * 8, z);
+            const int nb = mine - base < 64 ? mine - base : 64;
+            for (int j = 0; j < nb; ++j) {
+                const int r0 = __builtin_amdgcn_readlane(r0_l, j);
+                const int part = __builtin_amdgcn_readlane(part_l, j);
+                if (r0 < 0 || r0 >= M) continue;
+                const int r1 = r0 + rows_full < M ? r0 + rows_full : M;
+                if (!XT) {
+                    uint16_t *dst = C + (int64_t)r0 * N;
+                    const int64_t n16 = (int64_t)(r1 - r0) * N / 8;
+                    const int64_t lo = per * part, hi = lo + per < n16 ? lo + per : n16;
+                    for (int64_t i = lo + tid; i < hi; i += 256) store_c16(dst + i * 8, z);
+                } else {
+                    const int cpr = (r1 - r0) / 8;  // 16-byte units per row (M % 8 == 0)
+                    const int64_t lo = per * part, hi = lo + per < N ? lo + per : N;
+                    for (int64_t t = lo + (tid >> 4); t < hi; t += 16)
+                        if ((tid & 15) < cpr) store_c16(C + t * M + r0 + (tid & 15) * 8, z);
+                }
             }
         }
     };

@@ -291,6 +291,30 @@ def test_bcsr_small_blocks_composite_empty_rows_rerun_and_identity(b):
     assert not C1[512:768].any()
 
 
+@pytest.mark.parametrize("entry", ["spmm", "xt"])
+@pytest.mark.parametrize("b", [128, 64, 32])
+def test_bcsr_mostly_empty_matrix_every_row_written(b, entry):
+    # hundreds of block-rows without a stored block (more than the launch has workgroups): their rows of the
+    # output are cleared in (span, part) items dealt over the workgroups, not span by span
+    m, k, N = 400 * 128 + 24, 1024, 5 * 512 + 8
+    a = synth.block_sparse_bernoulli(m, k, b, b, 0.97, seed=91 + b, dtype="bf16")
+    lens = np.add.reduceat(np.diff(a.row_ptr), np.arange(0, m, b))
+    assert (lens == 0).sum() * (b // 32 if b < 128 else 1) > 256
+    empty = np.repeat(lens == 0, b)[:m]
+    if entry == "spmm":
+        assert _plan_bn_b(a, b, N) == 512
+        B = synth.dense_normal(k, N, "bf16", seed=92)
+        C = gpu_spmm(a, "bcsr", b, b, B)
+    else:
+        X = synth.dense_normal(N, k, "bf16", seed=92)
+        B = np.ascontiguousarray(X.T)
+        C = np.ascontiguousarray(gpu_spmm_xt(a, b, X).T)
+    assert not C[empty].any()                                  # +0.0 in every column of every empty row
+    assert not ((C & 0x7F80) == 0x7F80).any()                  # and no element left unwritten (the poison is a NaN)
+    cols = np.r_[0:32, N // 2 - 16:N // 2 + 16, N - 32:N]
+    check_against_oracle(a, B, C, cols)
+
+
 @pytest.mark.parametrize("b", [64, 32])
 def test_bcsr_small_blocks_composite_equals_small_block_kernel_within_rounding(b):
     # the same handle on a width where the composite form is not used (too few tiles) gives the same columns up
