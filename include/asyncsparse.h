@@ -97,8 +97,9 @@ typedef enum { ASP_ARR_ROW_PTR = 0, ASP_ARR_COL_IDX = 1, ASP_ARR_VALUES = 2, ASP
 /* How asp_spmm would run for a dense width N (Section IV-C: tile-width selection).  bf16 BCSR picks, among its
  * tile widths 64 / 128 / 256 / 512 (512: tiles of 128 rows -- 128x128 blocks, or 128-row stacks of smaller blocks where
  * the handle keeps them -- with at least one tile per compute unit), the one with the
- * least padded width x cost per column, costs 135 / 96 / 74 / 64 (ties: the wider); fp32 BCSR and WCSR take the
- * widest of their widths that divides N, else the one that pads least. */
+ * least padded width x cost per column, costs 135 / 96 / 74 / 64 (ties: the wider), and then the next narrower
+ * width while non-empty block-rows x ceil(N / width) tiles are fewer than the GPU's compute units (256 assumed for
+ * host-only handles); fp32 BCSR and WCSR take the widest of their widths that divides N, else the one that pads least. */
 typedef struct {
     int32_t bn;          /* columns of B/C handled by one workgroup (BCSR) or one wave (WCSR) */
     int32_t n_tiles;     /* ceil(N / bn): tiles along N, the last one masked if bn does not divide N */

@@ -75,6 +75,8 @@ def _load():
     L.oracle_choose_bn.restype = i64
     L.oracle_choose_bn_weighted.argtypes = [i64, vp, vp, ctypes.c_int]
     L.oracle_choose_bn_weighted.restype = i64
+    L.oracle_choose_bn_filled.argtypes = [i64, vp, vp, ctypes.c_int, i64, i64]
+    L.oracle_choose_bn_filled.restype = i64
     _lib = L
     return L
 
@@ -173,3 +175,11 @@ def choose_bn_weighted(N, candidates, cost) -> int:
     w = np.ascontiguousarray(cost, dtype=np.int64)
     assert len(c) == len(w)
     return int(_load().oracle_choose_bn_weighted(N, _p(c), _p(w), len(c)))
+
+
+def choose_bn_filled(N, candidates, cost, rows, units) -> int:
+    """choose_bn_weighted, then the next narrower candidate while rows x ceil(N / BN) tiles are fewer than `units`."""
+    c = np.ascontiguousarray(candidates, dtype=np.int64)
+    w = np.ascontiguousarray(cost, dtype=np.int64)
+    assert len(c) == len(w)
+    return int(_load().oracle_choose_bn_filled(N, _p(c), _p(w), len(c), rows, units))

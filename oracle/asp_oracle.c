@@ -319,3 +319,28 @@ int64_t oracle_choose_bn_weighted(int64_t N, const int64_t *candidates, const in
     }
     return best;
 }
+
+/*
+ * The weighted choice followed by the launch-filling step of the library under test: while the chosen width
+ * gives fewer tiles (rows x ceil(N / BN)) than the machine has units to run them on, and a narrower candidate
+ * exists, take the next narrower candidate.  A widest candidate that is only admitted when it fills the machine
+ * is the caller's business (it leaves it out of the list otherwise).
+ * PARITY UNPINNED against the paper, which launches one thread block per tile and states no rule for launches
+ * smaller than the machine (Section IV-C discusses the width only through work per loaded tile and padding):
+ * pinned by hand arithmetic and by the properties that follow from the definition (never wider than the
+ * weighted choice; equal to it when that already fills the machine; otherwise the widest narrower candidate
+ * that fills it, or the narrowest).
+ */
+int64_t oracle_choose_bn_filled(int64_t N, const int64_t *candidates, const int64_t *cost, int n_candidates,
+                                int64_t rows, int64_t units)
+{
+    int64_t bn = oracle_choose_bn_weighted(N, candidates, cost, n_candidates);
+    for (;;) {
+        if (rows * (oracle_padded_width(N, bn) / bn) >= units) return bn;
+        int64_t narrower = -1;
+        for (int c = 0; c < n_candidates; ++c)
+            if (candidates[c] < bn && candidates[c] > narrower) narrower = candidates[c];
+        if (narrower < 0) return bn;
+        bn = narrower;
+    }
+}

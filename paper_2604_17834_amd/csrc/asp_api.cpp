@@ -88,6 +88,10 @@ static asp_status_t create_impl(const asp_config_t *cfg, int64_t m, int64_t k, i
         h->task_cols = 0;
         csr_to_bcsr(m, k, row_ptr, col_idx, values, es, cfg->b_row, cfg->b_col, h->hb);
         h->n_units = (int64_t)h->hb.block_col_idx.size();
+        // (the plan counts tiles of non-empty block-rows, also for host-only handles, which get no schedule)
+        h->hb.n_nonempty = 0;
+        for (size_t r = 0; r + 1 < h->hb.block_row_ptr.size(); ++r)
+            h->hb.n_nonempty += h->hb.block_row_ptr[r + 1] > h->hb.block_row_ptr[r] ? 1 : 0;
         // Smaller blocks: the kernel for 128-row tiles on the composite form (asp_convert.cpp) beats the small-block
         // kernel, which reads twice / four times the LDS bytes per MFMA, until the zero fill outweighs that.
         // Measured on 8192 x 8192 matrices with geometric block-row lengths (N = 65536) at 50 / 75 / 90 / 95 / 99 %

@@ -323,7 +323,7 @@ def test_bcsr_small_blocks_composite_equals_small_block_kernel_within_rounding(b
     B = synth.dense_normal(a.k, 8192, "bf16", seed=66)
     h = asp.asp_create_from_csr("bcsr", "bf16", b, b, a.m, a.k, a.row_ptr, a.col_idx, a.values)
     try:
-        assert asp.asp_plan_spmm(h, 8192).bn == 512 and asp.asp_plan_spmm(h, 256).bn == 256
+        assert asp.asp_plan_spmm(h, 8192).bn == 512 and asp.asp_plan_spmm(h, 256).bn < 512   # the small-block kernel
         Cw = gpu_spmm(a, "bcsr", b, b, B, handle=h)
         Cn = gpu_spmm(a, "bcsr", b, b, np.ascontiguousarray(B[:, 1024:1280]), handle=h)
     finally:

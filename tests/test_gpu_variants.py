@@ -27,8 +27,8 @@ VARIANTS = [
     ({"ASP_BCSR_BN": "64"}, "bcsr_gate_proj", 2048, "", 64),
     ({"ASP_BCSR_BN": "256", "ASP_BCSR_SCHEDULE": "atomic"}, "bcsr_gate_proj", 2048, "", 256),  # tiles pulled from atomic counters
     ({"ASP_BCSR_BN": "256", "ASP_BCSR_SCHEDULE": "atomic"}, "bcsr_gate_proj", 16384 + 64, "", 256),  # ... with a masked tail tile
-    ({"ASP_BCSR_BN": "256", "ASP_BCSR_SCHEDULE": "atomic"}, "bcsr_down_proj", 2048, "", 256),     # ... 28 long block-rows
-    ({"ASP_BCSR_BN": "256", "ASP_BCSR_SCHEDULE": "atomic"}, "bcsr_sweep_b128_s95", 1024, "", 256),  # ... empty block-rows, geometric lengths
+    ({"ASP_BCSR_BN": "256", "ASP_BCSR_SCHEDULE": "atomic"}, "bcsr_down_proj", 4096, "", 256),     # ... 28 long block-rows
+    ({"ASP_BCSR_BN": "256", "ASP_BCSR_SCHEDULE": "atomic"}, "bcsr_sweep_b128_s95", 2048, "", 256),  # ... empty block-rows, geometric lengths
     ({"ASP_BCSR_BN": "256", "ASP_BCSR_GROUP_N": "1"}, "bcsr_gate_proj", 2048, "", 256),
     ({"ASP_BCSR_BN": "256", "ASP_BCSR_WGS_PER_CU": "1"}, "bcsr_gate_proj", 2048, "", 256),
     ({"ASP_BCSR_XCD_AWARE": "0"}, "bcsr_gate_proj", 2048, "", 512),                          # tiles dealt without regard to XCDs

@@ -222,7 +222,7 @@ def test_plan_follows_tile_width_rule():
             p = asp.asp_plan_spmm(h, N)
             if N % 8 == 0:
                 assert p.vectorized == 1
-                assert p.bn == oracle.choose_bn_weighted(N, [64, 128, 256], COST[:3])
+                assert p.bn == oracle.choose_bn_filled(N, [64, 128, 256], COST[:3], 2, 256)   # 2 block-rows, 256 units
             else:
                 assert p.vectorized == 0 and p.bn == 64
             assert p.n_tiles == -(-N // p.bn) and p.padded_n == oracle.padded_width(N, p.bn)
@@ -235,7 +235,21 @@ def test_plan_follows_tile_width_rule():
     try:
         for N, cands in ((16384, [64, 128, 256, 512]), (8192, [64, 128, 256, 512]), (4096, [64, 128, 256]), (8192 + 64, [64, 128, 256, 512]), (16448, [64, 128, 256, 512]), (1104, [64, 128, 256])):
             p = asp.asp_plan_spmm(h, N)
-            assert p.bn == oracle.choose_bn_weighted(N, cands, COST[:len(cands)]), (N, p.bn)
+            assert p.bn == oracle.choose_bn_filled(N, cands, COST[:len(cands)], 16, 256), (N, p.bn)
+        # a launch that would leave compute units without a tile takes narrower tiles: 16 block-rows need 16 tiles
+        # along N to fill 256 units
+        assert [asp.asp_plan_spmm(h, N).bn for N in (4096, 2048, 1024, 512, 64)] == [256, 128, 64, 64, 64]
+    finally:
+        asp.asp_destroy(h)
+    # block-rows without a stored block are no tiles: they do not count
+    a = synth.block_sparse_bernoulli(64 * 128, 256, 128, 128, 0.0, 2)
+    keep = (np.repeat(np.arange(a.m), np.diff(a.row_ptr)) // 128) % 4 == 0      # 16 of 64 block-rows keep their blocks
+    rp = np.zeros(a.m + 1, dtype=np.int64)
+    np.add.at(rp, np.repeat(np.arange(a.m), np.diff(a.row_ptr))[keep] + 1, 1)
+    h = asp.asp_create_from_csr("bcsr", "bf16", 128, 128, a.m, a.k, np.cumsum(rp).astype(np.int32), a.col_idx[keep],
+                                a.values[keep], flags=HOST)
+    try:
+        assert [asp.asp_plan_spmm(h, N).bn for N in (4096, 2048, 1024)] == [256, 128, 64]
     finally:
         asp.asp_destroy(h)
 
@@ -265,8 +279,8 @@ def test_tile_width_costs_are_the_measured_time_ratios_and_the_rule_meets_the_pa
     try:
         for N in (8192, 16384, 65536, 512 * 33):
             assert asp.asp_plan_spmm(h, N).bn == oracle.choose_bn(N, [64, 128, 256, 512]) == 512
-        for N in (256, 1024, 2048, 4096):     # too few 512-wide tiles for every compute unit: 256 is the widest
-            assert asp.asp_plan_spmm(h, N).bn == oracle.choose_bn(N, [64, 128, 256]) == 256
+        # too few 512-wide tiles for every compute unit: 256 is the widest (and 16 x 16 tiles of it fill the 256 units)
+        assert asp.asp_plan_spmm(h, 4096).bn == oracle.choose_bn(4096, [64, 128, 256]) == 256
     finally:
         asp.asp_destroy(h)
 

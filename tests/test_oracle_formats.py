@@ -71,6 +71,37 @@ def test_golden_tile_width(golden_dir):
     assert oracle.choose_bn_weighted(130, cand, cost) == 256     # 256*74 = 18944 < 256*96 = 24576 < 192*135
 
 
+def test_tile_width_rule_with_the_launch_filling_step():
+    # oracle.choose_bn_filled = the weighted choice, then the next narrower candidate while rows x ceil(N / BN) tiles
+    # are fewer than the machine's units.  Not a rule of the paper (parity unpinned there): pinned by hand arithmetic
+    # and by what its definition implies.
+    cand, cost = [64, 128, 256], [135, 96, 74]
+    # 28 rows, N = 1024, 256 units: 28*4 = 112 < 256, 28*8 = 224 < 256, 28*16 = 448 -> 64
+    assert oracle.choose_bn_filled(1024, cand, cost, 28, 256) == 64
+    # N = 4096: 28*16 = 448 >= 256 -> the weighted choice stands
+    assert oracle.choose_bn_filled(4096, cand, cost, 28, 256) == oracle.choose_bn_weighted(4096, cand, cost) == 256
+    # N = 2048: 28*8 = 224 < 256 -> 128 (28*16 = 448)
+    assert oracle.choose_bn_filled(2048, cand, cost, 28, 256) == 128
+    # nothing fills the machine: the narrowest
+    assert oracle.choose_bn_filled(64, cand, cost, 2, 256) == 64
+    # ragged N: 16 rows, N = 1100 -> weighted 256 (5 tiles: 80 < 256) -> 128 (9: 144) -> 64 (18: 288)
+    assert oracle.choose_bn_filled(1100, cand, cost, 16, 256) == 64
+    # one unit: never narrower than the weighted choice
+    rng = np.random.default_rng(5)
+    for _ in range(300):
+        N, rows, units = int(rng.integers(1, 40000)), int(rng.integers(1, 400)), int(rng.choice([1, 64, 256, 304]))
+        w = oracle.choose_bn_weighted(N, cand, cost)
+        f = oracle.choose_bn_filled(N, cand, cost, rows, units)
+        assert f in cand and f <= w
+        assert oracle.choose_bn_filled(N, cand, cost, rows, 1) == w
+        tiles = lambda bn: rows * -(-N // bn)
+        if tiles(w) >= units:
+            assert f == w
+        else:   # every candidate between the two leaves the machine short; the result fills it, or is the narrowest
+            assert all(tiles(c) < units for c in cand if f < c <= w)
+            assert tiles(f) >= units or f == min(cand)
+
+
 # ------------------------------------------------------------------ BCSR
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("m,k,br,bc,density", [(64, 96, 16, 32, 0.02), (128, 128, 32, 32, 0.01),
