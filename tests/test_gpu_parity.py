@@ -315,6 +315,33 @@ def test_bcsr_mostly_empty_matrix_every_row_written(b, entry):
     check_against_oracle(a, B, C, cols)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_bcsr_random_large_shapes_every_path(seed):
+    # seeded random shapes large enough for the 128 x 512-tile kernel: every block size, ragged M / K / N, Bernoulli and
+    # geometric masks from 30 % to 99.5 % block sparsity, both entries; whatever kernel the plan picks must match
+    rng = np.random.default_rng(7000 + seed)
+    b = int(rng.choice([128, 64, 32]))
+    m = int(rng.integers(20, 300)) * 128 + int(rng.choice([0, 0, 8, 40, 64]))
+    k = int(rng.integers(1, 16)) * 128 + int(rng.choice([0, 0, 32, 64]) if b < 128 else rng.choice([0, 0, 24]))
+    N = int(rng.integers(1, 10)) * 512 + int(rng.choice([0, 0, 8, 72, 256]))
+    sparsity = float(rng.choice([0.3, 0.7, 0.9, 0.97, 0.995]))
+    gen = synth.block_sparse_geometric if rng.random() < 0.4 else synth.block_sparse_bernoulli
+    xt = bool(rng.random() < 0.35)
+    a = gen(m, k, b, b, sparsity, seed=7100 + seed, dtype="bf16")
+    if xt:
+        X = synth.dense_normal(N, k, "bf16", seed=7200 + seed)
+        B = np.ascontiguousarray(X.T)
+        C = np.ascontiguousarray(gpu_spmm_xt(a, b, X).T)
+    else:
+        B = synth.dense_normal(k, N, "bf16", seed=7200 + seed)
+        C = gpu_spmm(a, "bcsr", b, b, B)
+    assert not ((C & 0x7F80) == 0x7F80).any()                  # no element left unwritten (the poison is a NaN)
+    lens = np.add.reduceat(np.diff(a.row_ptr), np.arange(0, a.m, b))
+    assert not C[np.repeat(lens == 0, b)[:a.m]].any()          # rows of empty block-rows are +0.0 everywhere
+    cols = np.unique(np.r_[0:16, rng.integers(0, N, 32), N - 16:N])
+    check_against_oracle(a, B, C, cols)
+
+
 @pytest.mark.parametrize("b", [64, 32])
 def test_bcsr_small_blocks_composite_equals_small_block_kernel_within_rounding(b):
     # the same handle on a width where the composite form is not used (too few tiles) gives the same columns up
