@@ -17,6 +17,10 @@
  *     is a WCSR handle whose split windows go through the handle's scratch
  *     buffer (asp_reserve): those calls must be ordered on one stream; calls
  *     of asp_spmm_static_scratch share one scratch array per GPU in the same way.
+ *   - asp_spmm, asp_spmm_xt and asp_spmm_static_scratch only launch kernels on
+ *     the caller's stream (no allocation, no memset, no host synchronisation),
+ *     so they may be recorded into a HIP graph; handle creation, asp_reserve
+ *     and asp_destroy allocate or free and may not.
  *   - The library needs a gfx950 GPU for everything except the calls marked
  *     "host only".  There is no CPU fallback for the product.
  */
