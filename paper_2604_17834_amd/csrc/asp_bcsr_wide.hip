@@ -28,8 +28,8 @@
 // spare buffer until the next step's barrier, and a finished tile stages its output there, without
 // an extra barrier.  Slices are requested two full steps before they are waited for.
 //
-// Tiles with no stored block are not part of the stream (their rows of C are cleared by a small
-// separate kernel).  At the end of its stream a workgroup keeps requesting the last block again (into
+// Tiles with no stored block are not part of the stream (their rows of C are cleared by the same
+// workgroups once their streams have ended).  At the end of its stream a workgroup keeps requesting the last block again (into
 // free buffers, never read), so every step issues the same loads and the wait counts are constants.
 // Scheduling, swizzling, store accounting: as in the 64 x 128 kernel.
 #include <cstdlib>
