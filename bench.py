@@ -187,9 +187,9 @@ def run_workload(name, steps, warmup, torch, asp, synth, with_cpu_baseline, cpu_
     roof["frac"] = roof["achieved"] / roof["peak"]
     if fmt == "bcsr" and dt == "bf16":
         # (counter evidence, not measured in this run: profiles/bench_default_pmc.txt)
-        roof["limiter"] = ("0.56 of the time is the instruction stream of one wave per SIMD (kernel without loads and stores), "
-                           "the rest memory: reads in flight per L1 (about 120 lines of 128 B per CU) x their latency, and the "
-                           "stores of C; the matrix cores are busy 0.40 of the cycles on the 90 %-sparse projection")
+        roof["limiter"] = ("the memory side shared by the compute units: 1.68e9 B per launch (2.2 x compulsory; the 4 MB L2 of an "
+                           "XCD holds half of the 7.3 MB slab of B its workgroups share) at 6.5-6.7 TB/s; on half of the compute units "
+                           "the same launch is 1.27 x slower, not 2 x; matrix cores busy 0.40 of the cycles")
     roof["traffic"], traffic_kernel = _measured_traffic(name)
     if traffic_kernel:
         roof["traffic_source"] = "profiles/hbm_traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled), kernel " + traffic_kernel
@@ -285,6 +285,8 @@ ABLATION = [
     ("  same, 128x128 tiles", {"ASP_BCSR_BN": "128"}),
     ("  same, 128x64 tiles", {"ASP_BCSR_BN": "64"}),
     ("+ 128x128 wave tiles, one wave per SIMD, hand-ordered issue, 128x512 tiles (default)", {}),
+    ("  same on 128 of the 256 compute units", {"ASP_BCSR_WORKGROUPS": "128"}),
+    ("  same on 64 of the 256 compute units", {"ASP_BCSR_WORKGROUPS": "64"}),
     ("  same, tiles dealt without regard to XCDs", {"ASP_BCSR_XCD_AWARE": "0"}),
     ("  same, 1 N-tile per group", {"ASP_BCSR_GROUP_N": "1"}),
     ("  same, 4 N-tiles per group", {"ASP_BCSR_GROUP_N": "4"}),

@@ -30,6 +30,7 @@ const Switches &switches() {
         s.bcsr_regstage = is("ASP_BCSR_KERNEL", "regstage");
         s.bcsr_group_n = num("ASP_BCSR_GROUP_N", 0);
         s.bcsr_wgs_per_cu = num("ASP_BCSR_WGS_PER_CU", 0);
+        s.bcsr_workgroups = num("ASP_BCSR_WORKGROUPS", 0);
         s.bcsr_xcd_aware = num("ASP_BCSR_XCD_AWARE", 1) != 0;
         s.bcsr_atomic = is("ASP_BCSR_SCHEDULE", "atomic");
         s.xt_generic = is("ASP_BCSR_XT", "generic");

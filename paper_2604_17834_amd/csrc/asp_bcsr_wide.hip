@@ -676,6 +676,10 @@ static void launch_wide(const asp_handle *h, const void *B, void *C, int64_t N, 
     const int64_t n_rows = op.n_rows;
     int64_t workers = h->n_cus;  // one resident workgroup per CU: the ring takes the whole LDS
     if (workers > n_rows * n_tiles) workers = n_rows * n_tiles;
+    // benchmarking switch: fewer resident workgroups, i.e. part of the compute units idle (the schedule's 16 lists
+    // per XCD stay balanced for 32, 16 or 8 workgroups per XCD)
+    const int env_workers = switches().bcsr_workgroups;
+    if (env_workers > 0 && env_workers < workers) workers = env_workers;
     workers = std::max<int64_t>(8, workers / 8 * 8);  // the same number of workgroups on every XCD
     const int env_xcd = switches().bcsr_xcd_aware ? 1 : 0;  // benchmarking switch: 0 = ignore the XCDs when dealing tiles
     XcdRuns runs = cut_runs(*op.weight_prefix, n_rows, n_tiles, group_n);

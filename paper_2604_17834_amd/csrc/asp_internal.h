@@ -33,6 +33,7 @@ struct Switches {
     bool bcsr_regstage;   // ASP_BCSR_KERNEL=regstage: the synchronous register-staged kernel
     int bcsr_group_n;     // ASP_BCSR_GROUP_N=<n>: N-tiles walked together (0: the kernels' defaults, 2 and 4)
     int bcsr_wgs_per_cu;  // ASP_BCSR_WGS_PER_CU=<n>: resident workgroups of the ring kernel (0: as many as LDS allows)
+    int bcsr_workgroups;  // ASP_BCSR_WORKGROUPS=<n>: resident workgroups of the 128x512-tile kernel (0: one per compute unit)
     bool bcsr_xcd_aware;  // ASP_BCSR_XCD_AWARE=0: deal tiles without regard to XCDs
     bool bcsr_atomic;     // ASP_BCSR_SCHEDULE=atomic: tiles pulled from per-XCD atomic counters (ring kernel, 128x256)
     bool xt_generic;      // ASP_BCSR_XT=generic: asp_spmm_xt without matrix cores

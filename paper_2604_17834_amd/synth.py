@@ -282,6 +282,11 @@ def workload(name: str, scale: float = 1.0):
         pct = int(mm.group(1))
         a = block_sparse_bernoulli(18944, 3584, blk, blk, pct / 100.0, seed=1040 + pct, dtype=dt or BF16)
         return a, "bcsr", blk, blk, max(256, int(16384 * s)), dt or BF16, 1005
+    mm = re.match(r"^bcsr_gate_proj_k(\d+)$", name)
+    if mm:                              # the projection's rows and sparsity with another inner dimension K
+        kk = int(mm.group(1))
+        a = block_sparse_bernoulli(18944, kk, blk, blk, 0.90, seed=1060, dtype=dt or BF16)
+        return a, "bcsr", blk, blk, max(256, int(16384 * s)), dt or BF16, 1005
     if name == "bcsr_small":            # config 1
         a = block_sparse_bernoulli(1024, 1024, 64, 64, 0.90, seed=1001, dtype=dt or BF16)
         return a, "bcsr", 64, 64, 256, dt or BF16, 1004

@@ -31,6 +31,8 @@ VARIANTS = [
     ({"ASP_BCSR_BN": "256", "ASP_BCSR_SCHEDULE": "atomic"}, "bcsr_sweep_b128_s95", 2048, "", 256),  # ... empty block-rows, geometric lengths
     ({"ASP_BCSR_BN": "256", "ASP_BCSR_GROUP_N": "1"}, "bcsr_gate_proj", 2048, "", 256),
     ({"ASP_BCSR_BN": "256", "ASP_BCSR_WGS_PER_CU": "1"}, "bcsr_gate_proj", 2048, "", 256),
+    ({"ASP_BCSR_WORKGROUPS": "128"}, "bcsr_gate_proj", 2048, "", 512),                       # half of the compute units idle
+    ({"ASP_BCSR_WORKGROUPS": "64"}, "bcsr_gate_proj_b64", 2048 + 72, "", 512),               # ... composite form, masked tail
     ({"ASP_BCSR_XCD_AWARE": "0"}, "bcsr_gate_proj", 2048, "", 512),                          # tiles dealt without regard to XCDs
     ({"ASP_BCSR_GROUP_N": "1"}, "bcsr_gate_proj", 2048, "", 512),
     ({"ASP_BCSR_GROUP_N": "4"}, "bcsr_gate_proj", 2048, "", 512),

@@ -374,7 +374,7 @@ def test_every_benchmarking_switch_has_a_gpu_parity_case():
     readers = [f for f, text in srcs.items() if "getenv" in text]
     assert [os.path.basename(f) for f in readers] == ["asp_api.cpp"]
     names = set(re.findall(r'"(ASP_(?:BCSR|WCSR)_[A-Z_]+)"', srcs[readers[0]]))
-    assert len(names) == 9
+    assert len(names) == 10
     cases = open(os.path.join(ROOT, "tests", "test_gpu_variants.py")).read()
     for n in names:
         assert '"%s"' % n in cases, n
